@@ -177,7 +177,7 @@ def gemm_at(At: np.ndarray, B: np.ndarray) -> np.ndarray:
 def gemm_rows_masked(A: np.ndarray, row_mask: np.ndarray, B: np.ndarray) -> np.ndarray:
     """C = diag(row_mask != 0) . A . B : rows outside the mask are zero rows whatever A holds there
     (padding tokens, Section 2.1 "Dynamic Sequence Length"); their outputs are exactly zero."""
-    Af = to_f64(A) * (np.asarray(row_mask) != 0)[:, None]
+    Af = np.where((np.asarray(row_mask) != 0)[:, None], to_f64(A), 0.0)   # padding may hold NaN/Inf
     return np.matmul(Af, to_f64(B))
 
 
