@@ -1,0 +1,323 @@
+// pit_sparse_attn: dynamic sparse attention with the key axis as PIT-axis (paper Section 5.1,
+// Longformer; Table 1, BatchMatMul).  Micro-tile = 32 queries x 1 key.
+//
+//   1. pit_build_index on the [S x S] byte mask (32 x 1 micro-tiles, PIT-axis = keys) gives, for
+//      every block of 32 queries, the ascending list of keys at least one of them attends to, and
+//      per listed key a 32-bit word saying which of the 32 queries do.
+//   2. One workgroup per (query block, head); its 4 wavefronts take the key list in chunks of 32
+//      keys, round-robin, each with its own running softmax state, merged at the end.
+//      Per chunk (everything is laid out so that lane % 32 == query):
+//        SRead   K rows of the listed keys go straight from global memory into MFMA A-operands
+//                (a K row is d-contiguous, which is what the operand wants); V rows are gathered
+//                into LDS as [key][d].
+//        S^T   = K' . Q^T           4 x v_mfma_f32_32x32x16 (input type), fp32
+//        mask, running max / sum per query, P^T = exp2(S^T*c - m)        fp32, in registers
+//        O^T  += V'^T . P^T         4 x v_mfma_f32_32x32x16_f16; V'^T operands come from LDS with
+//                the transposing read; the accumulator layout of S^T is already the B-operand
+//                layout of this product up to a permutation of the keys inside the chunk, which is
+//                free because keys are a PIT-axis here (the same permutation is applied to V').
+//      SWrite is a plain store: queries of a block are contiguous.
+// P and V enter the second product as fp16 (11-bit significand): bf16 P would by itself cost about
+// 1.7e-3 relative Frobenius error.  bf16 V converts to fp16 exactly for 2^-24 <= |v| <= 65504
+// (smaller magnitudes lose bits or flush, larger overflow; neither occurs for activations of
+// order 1).
+#include "pit_common.hpp"
+
+namespace pit {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef short v4i16_t __attribute__((__vector_size__(8)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+#define PIT_LDS __attribute__((address_space(3)))
+
+constexpr int QB = 32;          // queries per block (micro-tile height)
+constexpr int KC = 32;          // keys per chunk
+constexpr int HD = 64;          // head dimension
+constexpr int V_TILE_BYTES = KC * HD * 2;   // 4 KiB
+
+template <bool BF>
+__device__ __forceinline__ f32x16_t mfma_in(const uint4& a, const uint4& b, const f32x16_t& c) {
+  if constexpr (BF)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16_t mfma_f16(const uint4& a, const uint4& b, const f32x16_t& c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ uint32_t pack_f16x2(float a, float b) {
+  const uint16_t lo = __builtin_bit_cast(uint16_t, (_Float16)a), hi = __builtin_bit_cast(uint16_t, (_Float16)b);
+  return (uint32_t)lo | ((uint32_t)hi << 16);
+}
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
+  const float lo = __builtin_bit_cast(float, v << 16), hi = __builtin_bit_cast(float, v & 0xFFFF0000u);
+  return pack_f16x2(lo, hi);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// byte offset of 16-byte chunk c16 (8 d) of key row r inside a V tile [32 keys][64 d]; the two
+// 64-byte halves of a row are swapped on rows with (r >> 1) odd so that the 4 consecutive rows a
+// transposing read touches land in 4 different quarters of the 256-byte bank row.
+__device__ __forceinline__ uint32_t v_off(int r, int c16) {
+  return (uint32_t)(r * 128 + ((((c16 >> 2) ^ ((r >> 1) & 1)) << 6) | ((c16 & 3) << 4)));
+}
+
+// OT: 0 = fp32, 1 = bf16, 2 = fp16 output
+template <bool BF, int OT>
+__global__ void __launch_bounds__(256)
+k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+              const int32_t* __restrict__ seg_ptr, const int32_t* __restrict__ idx, const uint32_t* __restrict__ bits,
+              void* __restrict__ O, int S, float scale_log2e) {
+  __shared__ __attribute__((aligned(1024))) char s_v[4][V_TILE_BYTES];
+  __shared__ __attribute__((aligned(16))) uint32_t s_bits[4][KC];
+  __shared__ float s_merge[3][64][34];
+
+  const int qb = blockIdx.x, head = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int h = lane >> 5, ql = lane & 31;
+  const int list_begin = seg_ptr[qb];
+  const int list_len = seg_ptr[qb + 1] - list_begin;
+  const int nchunks = (list_len + KC - 1) / KC;
+  const int64_t head_off = (int64_t)head * S * HD;
+
+  // Q^T operand: lane holds query ql, d = 16*ks + 8*h + (0..7)
+  uint4 qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    qf[ks] = *reinterpret_cast<const uint4*>(Q + head_off + (int64_t)(qb * QB + ql) * HD + ks * 16 + h * 8);
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16_t o[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+
+  const uint32_t v_lds = (uint32_t)(uintptr_t)(PIT_LDS char*)s_v[wv];
+
+  for (int c0 = 0; c0 < nchunks; c0 += 4) {
+    const int c = c0 + wv;
+    const bool active = c < nchunks;          // uniform per wave
+    f32x16_t st;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) st[e] = 0.f;
+    if (active) {
+      const int kk = c * KC + ql;
+      const bool valid = kk < list_len;
+      const int key = valid ? idx[list_begin + kk] : -1;
+      if (h == 0) s_bits[wv][ql] = valid ? bits[list_begin + kk] : 0u;
+      // SRead K': rows straight into A-operands
+      uint4 kf[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        kf[ks] = make_uint4(0, 0, 0, 0);
+        if (valid) kf[ks] = *reinterpret_cast<const uint4*>(K + head_off + (int64_t)key * HD + ks * 16 + h * 8);
+      }
+      // SRead V': 32 rows x 128 B into LDS, 4 x 16 B per lane
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int x = it * 64 + lane;
+        const int r = x >> 3, c16 = x & 7;
+        const int krow = __shfl(key, r);
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (krow >= 0) v = *reinterpret_cast<const uint4*>(V + head_off + (int64_t)krow * HD + c16 * 8);
+        if constexpr (BF) {
+          v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y);
+          v.z = bf16x2_to_f16x2(v.z); v.w = bf16x2_to_f16x2(v.w);
+        }
+        *(PIT_LDS u32x4_t*)(uintptr_t)(v_lds + v_off(r, c16)) = __builtin_bit_cast(u32x4_t, v);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) st = mfma_in<BF>(kf[ks], qf[ks], st);
+    }
+    __syncthreads();
+    if (active) {
+      // st[j] = S^T[key 8*(j/4) + 4*h + j%4][query ql]
+      float mx = -INFINITY;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const u32x4_t bw = *(PIT_LDS u32x4_t*)(uintptr_t)((uint32_t)(uintptr_t)(PIT_LDS char*)&s_bits[wv][g * 8 + h * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool on = (bw[e] >> ql) & 1u;
+          const float s = on ? st[g * 4 + e] * scale_log2e : -INFINITY;
+          st[g * 4 + e] = s;
+          mx = fmaxf(mx, s);
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = exp2f(m_run - m_safe);
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = exp2f(st[e] - m_safe);
+        st[e] = p;
+        psum += p;
+      }
+      psum += __shfl_xor(psum, 32);
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+      // O^T += V'^T . P^T ; k-step t covers chunk keys 16t .. 16t+15 in the order the accumulator holds them
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        uint4 pb;
+        pb.x = pack_f16x2(st[8 * t + 0], st[8 * t + 1]);
+        pb.y = pack_f16x2(st[8 * t + 2], st[8 * t + 3]);
+        pb.z = pack_f16x2(st[8 * t + 4], st[8 * t + 5]);
+        pb.w = pack_f16x2(st[8 * t + 6], st[8 * t + 7]);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          const int r0 = 16 * t + 4 * h + ((lane & 15) >> 2);
+          const int col = dt * 32 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+          const int r1 = r0 + 8;
+          const uint32_t a0 = v_lds + (uint32_t)(r0 * 128 + ((((col >> 5) ^ ((r0 >> 1) & 1)) << 6) | ((col & 31) * 2)));
+          const uint32_t a1 = v_lds + (uint32_t)(r1 * 128 + ((((col >> 5) ^ ((r1 >> 1) & 1)) << 6) | ((col & 31) * 2)));
+          const uint2 lo = __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((PIT_LDS v4i16_t*)(uintptr_t)a0));
+          const uint2 hi = __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((PIT_LDS v4i16_t*)(uintptr_t)a1));
+          o[dt] = mfma_f16(make_uint4(lo.x, lo.y, hi.x, hi.y), pb, o[dt]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // merge the 4 wavefronts' partial (m, l, O) per lane; wave 0 finishes
+  if (wv > 0) {
+    float* dst = s_merge[wv - 1][lane];
+    dst[0] = m_run;
+    dst[1] = l_run;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dst[2 + t * 16 + e] = o[t][e];
+  }
+  __syncthreads();
+  if (wv != 0) return;
+  float m_all = m_run;
+#pragma unroll
+  for (int w = 0; w < 3; ++w) m_all = fmaxf(m_all, s_merge[w][lane][0]);
+  const float m_safe = m_all == -INFINITY ? 0.f : m_all;
+  float a = exp2f(m_run - m_safe);
+  float l_all = l_run * a;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[t][e] *= a;
+#pragma unroll
+  for (int w = 0; w < 3; ++w) {
+    const float* src = s_merge[w][lane];
+    a = exp2f(src[0] - m_safe);
+    l_all += src[1] * a;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[t][e] += src[2 + t * 16 + e] * a;
+  }
+  const float inv = l_all > 0.f ? 1.f / l_all : 0.f;
+  // o[dt][4*g + e] = O[query ql][d = 32*dt + 8*g + 4*h + e]
+  const int64_t row = head_off + (int64_t)(qb * QB + ql) * HD;
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d = dt * 32 + g * 8 + h * 4;
+      const float v0 = o[dt][4 * g] * inv, v1 = o[dt][4 * g + 1] * inv, v2 = o[dt][4 * g + 2] * inv, v3 = o[dt][4 * g + 3] * inv;
+      if constexpr (OT == 0) {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(O) + row + d) = make_float4(v0, v1, v2, v3);
+      } else if constexpr (OT == 1) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16_rne(v0) | ((uint32_t)f32_to_bf16_rne(v1) << 16);
+        pk.y = (uint32_t)f32_to_bf16_rne(v2) | ((uint32_t)f32_to_bf16_rne(v3) << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(O) + row + d) = pk;
+      } else {
+        uint2 pk;
+        pk.x = pack_f16x2(v0, v1);
+        pk.y = pack_f16x2(v2, v3);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(O) + row + d) = pk;
+      }
+    }
+}
+
+struct AttnWs {
+  size_t seg_ptr_off, idx_off, bits_off, build_off, total;
+  int nseg, cap;
+};
+AttnWs attn_layout(int S) {
+  AttnWs w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) & ~(size_t)255; return at; };
+  w.nseg = S / QB;
+  w.cap = w.nseg * S;
+  w.seg_ptr_off = take((size_t)(w.nseg + 1) * 4);
+  w.idx_off = take((size_t)(w.cap > 0 ? w.cap : 1) * 4);
+  w.bits_off = take((size_t)(w.cap > 0 ? w.cap : 1) * 4);
+  w.build_off = take(pit_build_index_workspace(S, S, QB, 1, 1, 1));
+  w.total = o;
+  return w;
+}
+
+}  // namespace
+}  // namespace pit
+
+using namespace pit;
+
+extern "C" size_t pit_sparse_attn_workspace(int H, int S, int D) {
+  if (H < 0 || S < 0 || D != HD || S % QB) return 0;
+  return attn_layout(S).total;
+}
+
+extern "C" int pit_sparse_attn(const void* d_Q, const void* d_K, const void* d_V, const uint8_t* d_mask,
+                               void* d_O, int o_dt, int H, int S, int D, float scale, int in_dt,
+                               void* d_ws, size_t ws_bytes, pit_stream stream) {
+  if (in_dt != PIT_BF16 && in_dt != PIT_F16) return PIT_EINVAL;
+  if (o_dt != PIT_F32 && o_dt != PIT_BF16 && o_dt != PIT_F16) return PIT_EINVAL;
+  if (H < 0 || S < 0) return PIT_ESHAPE;
+  if (D != HD || S % QB) return PIT_ESHAPE;
+  if (H == 0 || S == 0) return PIT_OK;
+  if (H > 65535) return PIT_ESHAPE;
+  if (!d_Q || !d_K || !d_V || !d_mask || !d_O || !d_ws) return PIT_EINVAL;
+  if (!aligned(d_Q, 16) || !aligned(d_K, 16) || !aligned(d_V, 16) || !aligned(d_O, 16) || !aligned(d_ws, 256)) return PIT_EINVAL;
+  const AttnWs L = attn_layout(S);
+  if (ws_bytes < L.total) return PIT_ECAPACITY;
+  char* ws = reinterpret_cast<char*>(d_ws);
+  pit_index ix;
+  ix.seg_ptr = reinterpret_cast<int32_t*>(ws + L.seg_ptr_off);
+  ix.idx = reinterpret_cast<int32_t*>(ws + L.idx_off);
+  ix.bits = reinterpret_cast<uint32_t*>(ws + L.bits_off);
+  ix.nseg = L.nseg;
+  ix.cap = L.cap;
+  int rc = pit_build_index(d_mask, PIT_U8, S, S, S, QB, 1, 1, &ix, ws + L.build_off, L.total - L.build_off, stream);
+  if (rc != PIT_OK) return rc;
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const float c = scale * 1.4426950408889634f;
+  const uint16_t* q = reinterpret_cast<const uint16_t*>(d_Q);
+  const uint16_t* k = reinterpret_cast<const uint16_t*>(d_K);
+  const uint16_t* v = reinterpret_cast<const uint16_t*>(d_V);
+  dim3 grid((unsigned)L.nseg, (unsigned)H);
+#define PIT_ATTN_LAUNCH(BF, OT) \
+  hipLaunchKernelGGL((k_sparse_attn<BF, OT>), grid, dim3(256), 0, st, q, k, v, ix.seg_ptr, ix.idx, ix.bits, d_O, S, c)
+  const int ot = o_dt == PIT_F32 ? 0 : (o_dt == PIT_BF16 ? 1 : 2);
+  if (in_dt == PIT_BF16) {
+    if (ot == 0) PIT_ATTN_LAUNCH(true, 0); else if (ot == 1) PIT_ATTN_LAUNCH(true, 1); else PIT_ATTN_LAUNCH(true, 2);
+  } else {
+    if (ot == 0) PIT_ATTN_LAUNCH(false, 0); else if (ot == 1) PIT_ATTN_LAUNCH(false, 1); else PIT_ATTN_LAUNCH(false, 2);
+  }
+#undef PIT_ATTN_LAUNCH
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
+}

@@ -138,6 +138,10 @@ def pit_build_index(src: torch.Tensor, mt_rows: int, mt_cols: int, pit_dim: int,
     return out
 
 
+def pit_build_route_index_workspace(T, E) -> int:
+    return _lib.pit_build_route_index_workspace(T, E)
+
+
 def pit_build_route_index(expert_id: torch.Tensor, E: int, out: PitIndex | None = None,
                           status: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> PitIndex:
     assert expert_id.dtype == torch.int32 and expert_id.is_contiguous()
@@ -145,7 +149,7 @@ def pit_build_route_index(expert_id: torch.Tensor, E: int, out: PitIndex | None 
     if out is None:
         out = PitIndex.empty(E, T, False, expert_id.device)
     if ws is None:
-        ws = torch.empty(max(_lib.pit_build_route_index_workspace(T, E), 8), dtype=torch.uint8, device=expert_id.device)
+        ws = torch.empty(max(pit_build_route_index_workspace(T, E), 8), dtype=torch.uint8, device=expert_id.device)
     ci = out.c()
     _check(_lib.pit_build_route_index(expert_id.data_ptr(), T, E, ctypes.byref(ci), _ptr(status), ws.data_ptr(),
                                       ws.numel(), _stream()), "pit_build_route_index")
