@@ -1,5 +1,6 @@
 // pit_sread_gemm: host-side validation and launch of the SRead/MFMA/SWrite kernel.
 #include "pit_gemm.hpp"
+#include <cstdlib>
 
 namespace pit {
 namespace {
@@ -271,6 +272,411 @@ k_sread_gemm(const GemmArgs g) {
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Pipelined kernel.  Every operand tile is K-MINOR in LDS ([128 x][64 k], 128 B per row) and is read
+// with ds_read_b128 (about twice the rate of the 8-byte transposing read).  K-major sources (rows of
+// At and of B) are transposed in registers on their way in: a thread loads an 8 k x 8 column block
+// (8 x 16 B, one row each), interleaves the 16-bit elements with v_perm_b32 and writes 8 rows of
+// 16 B.  Global loads run D steps ahead in a register ring, so HBM/L2 latency is covered with a
+// single wavefront per SIMD.  The steady-state loop is branch-free: all loads are unconditional
+// (positions past the end of a list are clamped to its last entry and the rows are zeroed on the
+// way into LDS, in the last step only), index values are fetched one step before the loads that
+// use them and ahead of that step's data loads, so waiting for them never drains the data loads.
+//
+// Global loads are laid out so that 16 consecutive lanes read 256 contiguous bytes of one source
+// row (the address unit merges 4 neighbouring lanes into one 64-byte request; lanes that jump
+// between rows cost one request each, four times the address-unit time).
+//
+// LDS address of 16-byte chunk c (8 k) of tile row m, with a = m >> 4, h = (m >> 3) & 1, l = m & 7:
+//   256-byte bank row = a * 8 + c,   16-byte slot = h * 8 + ((l + a + c) & 7)
+// The LDS serves 16 lanes per clock and conflicts are decided by the slot.  All three access
+// shapes put 16 lanes on 16 different slots:
+//   operand read        16 consecutive rows (a fixed; h, l vary), one chunk
+//   transposing write   rows 8*cg + x for 16 consecutive cg (l = x fixed; a, h vary), one chunk
+//   straight write      rows m and m + 8 (h differs), all 8 chunks each
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t tile_off(int m, int c) {
+  const int a = m >> 4, h = (m >> 3) & 1, l = m & 7;
+  return (uint32_t)((((a << 3) | c) << 8) | (((h << 3) | ((l + a + c) & 7)) << 4));
+}
+
+// r[j] = 8 consecutive columns of k-row j (16-bit elements); out[x] = 8 consecutive k of column x
+__device__ __forceinline__ void transpose8x8_b16(const uint4 (&r)[8], uint4 (&out)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t lo[4], hi[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const uint32_t a = i == 0 ? r[2 * jj].x : i == 1 ? r[2 * jj].y : i == 2 ? r[2 * jj].z : r[2 * jj].w;
+      const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
+      lo[jj] = __builtin_amdgcn_perm(b, a, 0x05040100u);
+      hi[jj] = __builtin_amdgcn_perm(b, a, 0x07060302u);
+    }
+    out[2 * i] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    out[2 * i + 1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+  }
+}
+
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+// 16-byte load from global memory at a wave-uniform base plus a 32-bit per-lane byte offset.  The
+// explicit global address space keeps the access a global_load (a flat load would tie up both
+// memory counters and force full waits).
+__device__ __forceinline__ uint4 load16(const char* base, uint32_t byte_off) {
+  typedef const u32x4_t __attribute__((address_space(1))) * gptr_t;
+  const u32x4_t v = *(gptr_t)(uintptr_t)(reinterpret_cast<uintptr_t>(base) + byte_off);
+  return __builtin_bit_cast(uint4, v);
+}
+
+__device__ __forceinline__ u32x4_t lds_read_frag(uint32_t addr) {
+  return *(PIT_LDS u32x4_t*)(uintptr_t)addr;
+}
+template <bool BF>
+__device__ __forceinline__ f32x16_t mfma32v(const u32x4_t& a, const u32x4_t& b, const f32x16_t& c) {
+  if constexpr (BF)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+// KS = 1: 256 threads, one k-group.  KS = 2: 512 threads; two groups of 4 wavefronts work on the SAME
+// 128 x 128 tile, group g taking the g-th 64-wide half of every 128-wide k step with its own LDS
+// buffers and accumulators; the two partial tiles are added through LDS before SWrite.  That puts
+// two wavefronts on every SIMD (one can issue MFMAs while the other waits on the memory pipes)
+// without shrinking the tile or going through global memory.
+template <bool BF, bool GK, int EPI, int CT, int D, int KS, int ABL = 0>
+__global__ void __launch_bounds__(256 * KS)
+k_sread_gemm3(const GemmArgs g) {
+  static_assert(D == 2 || D == 4, "ring depth must divide the unroll factor 4");
+  static_assert(KS == 1 || KS == 2, "one or two k-groups");
+  constexpr int TKS = TK * KS;                     // k extent of one step of the whole workgroup
+  __shared__ __attribute__((aligned(1024))) char smem[KS * 2 * STAGE_BYTES];
+  __shared__ int s_rows_a[TM];
+  __shared__ int s_rows_c[TM];
+
+  const int tid_all = threadIdx.x;
+  const int grp = KS == 1 ? 0 : __builtin_amdgcn_readfirstlane(tid_all >> 8);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(PIT_LDS char*)smem + (uint32_t)grp * 2u * STAGE_BYTES;
+  const int tid = tid_all & 255, lane = tid & 63, wv = tid >> 6;
+  const int wm = wv >> 1, wn = wv & 1;
+  const int n0 = blockIdx.x * TN;
+
+  int seg, list_begin, list_len;
+  int k_begin = 0, k_len = 0;
+  if constexpr (GK) {
+    seg = blockIdx.y;
+    list_begin = g.seg_ptr[seg];
+    list_len = g.seg_ptr[seg + 1] - list_begin;
+  } else {
+    const int tile = blockIdx.y;
+    int acc = 0;
+    seg = -1;
+    int tile_in_seg = 0;
+    for (int s0 = 0; s0 < g.nseg; s0 += 64) {
+      const int s = s0 + lane;
+      int cnt = 0;
+      if (s < g.nseg) cnt = g.seg_ptr[s + 1] - g.seg_ptr[s];
+      const int nt = (cnt + TM - 1) / TM;
+      int inc = nt;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_up(inc, d);
+        if (lane >= d) inc += t;
+      }
+      const int total = __shfl(inc, 63);
+      if (tile < acc + total) {
+        const unsigned long long hit = __ballot(acc + inc > tile);
+        const int l = __builtin_ctzll(hit);
+        seg = s0 + l;
+        tile_in_seg = tile - (acc + __shfl(inc, l) - __shfl(nt, l));
+        break;
+      }
+      acc += total;
+    }
+    if (seg < 0) return;
+    const int sb = g.seg_ptr[seg];
+    const int cnt = g.seg_ptr[seg + 1] - sb;
+    list_begin = sb + tile_in_seg * TM;
+    list_len = min(TM, cnt - tile_in_seg * TM);
+    k_begin = g.slab_per_seg ? seg * g.slab : 0;
+    k_len = g.slab;
+    if (tid_all < TM) {
+      // rows past the end of the list read the list's last row (a valid address); their results
+      // are never stored
+      const int v = g.idx[list_begin + min(tid_all, list_len - 1)];
+      s_rows_a[tid_all] = g.a_gather ? v : list_begin + min(tid_all, list_len - 1);
+      s_rows_c[tid_all] = tid_all < list_len ? (g.c_scatter ? v : list_begin + tid_all) : -1;
+    }
+    __syncthreads();
+  }
+  seg = __builtin_amdgcn_readfirstlane(seg);
+  list_begin = __builtin_amdgcn_readfirstlane(list_begin);
+  list_len = __builtin_amdgcn_readfirstlane(list_len);
+
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int len = GK ? list_len : k_len;          // extent of the k loop (list entries or slab width)
+  const int nsteps = (len + TKS - 1) / TKS;
+  const int tail = len % TKS;                      // != 0: the last step is partial
+  const int kpos0 = grp * TK;                      // this group's offset inside a step
+
+  // ---- loader roles: threads 0..127 fill the A tile, threads 128..255 the B tile (wave-uniform)
+  const bool is_b = __builtin_amdgcn_readfirstlane(tid >> 7) != 0;
+  const int u = tid & 127;
+  const int t_cg = u & 15, t_kg = u >> 4;                               // transposing role: 8 k x 8 columns
+  const int s_chunk = u & 7, s_row = (((u >> 3) & 1) << 3) | (u >> 4);  // straight role (GATHER_M, A): rows r, r+8 per 16 lanes
+  const bool transposing = GK || is_b;
+
+  const char* a_bytes = reinterpret_cast<const char*>(g.A);
+  const char* b_bytes = reinterpret_cast<const char*>(g.B) + (int64_t)seg * g.b_seg_stride * 2;
+  const char* src = uniform_ptr(is_b ? b_bytes : a_bytes);
+  const uint32_t pitch = (uint32_t)((is_b ? g.ldb : g.lda) * 2);   // bytes per source row (< 2^24, checked on the host)
+  // transposing role: byte offset of this thread's 8 columns inside a source row
+  const uint32_t col_bytes = (uint32_t)(((GK && !is_b) ? seg * TM : n0) + t_cg * 8) * 2u;
+
+  uint32_t a_off[8];   // straight role: byte offset of (row of round j, this thread's chunk) at k step 0
+  if constexpr (!GK) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a_off[j] = __umul24((uint32_t)s_rows_a[j * 16 + s_row], pitch) + (uint32_t)(k_begin + s_chunk * 8) * 2u;
+  }
+
+  // LDS write offsets
+  uint32_t w_off[8];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) w_off[x] = transposing ? tile_off(t_cg * 8 + x, t_kg) : tile_off(x * 16 + s_row, s_chunk);
+  const uint32_t w_tile = is_b ? (uint32_t)A_TILE_BYTES : 0u;
+  // LDS read offsets.  For the 32-row block i of this wave and k-substep ks the operand address is
+  //   rdX[(ks + i) & 3] + i * 4096 + ks * 512
+  // (the slot rotates with a + c, and both the block and the substep add 2 to that sum).
+  uint32_t rd_a[4], rd_b[4];
+  {
+    const int m = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      rd_a[q] = tile_off(wm * 64 + m, hi + 2 * q) - (uint32_t)q * 512u;
+      rd_b[q] = tile_off(wn * 64 + m, hi + 2 * q) - (uint32_t)q * 512u + (uint32_t)A_TILE_BYTES;
+    }
+  }
+
+  uint4 R[D][8];
+  int k_use[8], k_pend[8];   // GATHER_K: list values for the step being issued / the one after
+  int k_ahead = 0;           // GATHER_K: one list entry on its way from global memory to the LDS ring
+
+  // GATHER_K keeps a sliding window of the k-list in LDS (16 steps x 64 entries).  Every 4th step
+  // each thread fetches one entry 12 steps ahead and stores it 3 steps later, so no load in the
+  // loop ever depends on a load issued less than 3 steps before it.
+  constexpr int KRING = 16 * TKS;
+  __shared__ __attribute__((aligned(32))) int s_kidx[GK ? KRING : 4];
+  const uint32_t kring = (uint32_t)(uintptr_t)(PIT_LDS char*)s_kidx;
+  auto list_at = [&](int pos) { return g.idx[list_begin + min(pos, list_len - 1)]; };
+  auto load_kid = [&](int step, int (&dst)[8]) {
+    const uint32_t a = kring + (uint32_t)(((step & 15) * TKS + kpos0 + t_kg * 8) * 4);
+    const u32x4_t lo = *(PIT_LDS u32x4_t*)(uintptr_t)a;
+    const u32x4_t hi = *(PIT_LDS u32x4_t*)(uintptr_t)(a + 16);
+    dst[0] = lo.x; dst[1] = lo.y; dst[2] = lo.z; dst[3] = lo.w;
+    dst[4] = hi.x; dst[5] = hi.y; dst[6] = hi.z; dst[7] = hi.w;
+  };
+  auto issue = [&](int step, uint4 (&r)[8]) {
+    if constexpr (GK) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) r[j] = load16(src, __umul24((uint32_t)k_use[j], pitch) + col_bytes);
+    } else {
+      if (is_b) {
+        const int base = k_begin + min(step * TKS + kpos0 + t_kg * 8, k_len - 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = load16(src, __umul24((uint32_t)(base + j), pitch) + col_bytes);
+      } else {
+        // byte distance from this thread's chunk at step 0; a chunk past the slab end re-reads the last one
+        const uint32_t kofs = (uint32_t)((min(step * TKS + kpos0 + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = load16(src, a_off[j] + kofs);
+      }
+    }
+  };
+  // zero what lies past the end of the k extent (last, partial step only)
+  auto zero_tail = [&](int step, uint4 (&r)[8]) {
+    if (transposing) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (step * TKS + kpos0 + t_kg * 8 + j >= len) r[j] = make_uint4(0, 0, 0, 0);
+    } else {
+      if (step * TKS + kpos0 + s_chunk * 8 >= len) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto stage = [&](int buf, int step, uint4 (&r)[8], bool may_be_last) {
+    if (may_be_last && tail != 0 && step == nsteps - 1) zero_tail(step, r);
+    const uint32_t t = lds0 + buf * STAGE_BYTES + w_tile;
+    if (transposing) {
+      uint4 o[8];
+      transpose8x8_b16(r, o);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) lds_write_b128(t, w_off[x], o[x]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) lds_write_b128(t, w_off[j], r[j]);
+    }
+  };
+  auto compute = [&](int buf) {
+    const uint32_t t = lds0 + buf * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4_t af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = lds_read_frag(t + rd_a[(ks + i) & 3] + i * 4096 + ks * 512);
+        bf[i] = lds_read_frag(t + rd_b[(ks + i) & 3] + i * 4096 + ks * 512);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32v<BF>(af[i], bf[j], acc[i][j]);
+    }
+  };
+
+  if (nsteps > 0) {
+    if constexpr (GK) {
+      // list window for steps 0..15
+      int v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = list_at(q * 256 * KS + tid_all);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) s_kidx[q * 256 * KS + tid_all] = v[q];
+      __syncthreads();
+    }
+    // prologue: steps 0 .. D-1 into the ring, step 0 into LDS, step D into the freed slot
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      if (s < nsteps) {
+        if constexpr (GK) load_kid(s, k_use);
+        issue(s, R[s]);
+      }
+    }
+    if constexpr (GK) {
+      load_kid(min(D, nsteps - 1), k_use);
+      load_kid(min(D + 1, nsteps - 1), k_pend);
+    }
+    stage(0, 0, R[0], true);
+    if (D < nsteps) issue(D, R[0]);
+    __syncthreads();
+    if (KS == 2 && grp == 1) __syncthreads();   // group 1 runs one barrier behind group 0 from here on
+
+    int it = 0;
+    // steady state, 4 steps per trip: every step here has step + 1 + D < nsteps; no conditionals
+    // around memory operations
+    for (; it + 4 + D < nsteps; it += 4) {
+#pragma unroll
+      for (int uu = 0; uu < 4; ++uu) {
+        const int step = it + uu;
+        if constexpr (GK) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) k_use[j] = k_pend[j];
+          load_kid(min(step + 2 + D, nsteps - 1), k_pend);
+          if (uu == 0) k_ahead = list_at((step + 12) * TKS + tid_all);
+          // the list fetch stays ahead of this step's data loads in program order: the memory
+          // counter is in-order, so waiting for it later never drains the younger data loads
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (GK) {
+          if (uu == 3) s_kidx[((step + 9) * TKS + tid_all) & (KRING - 1)] = k_ahead;   // entries of steps it+12 .. it+15
+        }
+        // KS == 2: the two groups run half a step out of phase (group 1 entered the loop one
+        // barrier late): while one feeds the matrix cores from LDS, the other moves the next
+        // tiles (global loads, transposes, LDS stores)
+        if constexpr (!(ABL & 1)) compute(uu & 1);
+        if (KS == 2) __syncthreads();
+        if constexpr (!(ABL & 2)) stage((uu + 1) & 1, step + 1, R[(uu + 1) % D], false);
+        if constexpr (!(ABL & 4)) issue(step + 1 + D, R[(uu + 1) % D]);
+        __syncthreads();
+      }
+    }
+    // drain
+    for (; it < nsteps; it += 4) {
+#pragma unroll
+      for (int uu = 0; uu < 4; ++uu) {
+        const int step = it + uu;
+        if (step >= nsteps) break;
+        if constexpr (GK) {
+          if (step + 1 + D < nsteps) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) k_use[j] = k_pend[j];
+            load_kid(min(step + 2 + D, nsteps - 1), k_pend);
+          }
+        }
+        compute(uu & 1);
+        if (KS == 2) __syncthreads();
+        if (step + 1 < nsteps) stage((uu + 1) & 1, step + 1, R[(uu + 1) % D], true);
+        if (step + 1 + D < nsteps) issue(step + 1 + D, R[(uu + 1) % D]);
+        __syncthreads();
+      }
+    }
+    if (KS == 2 && grp == 0) __syncthreads();   // pairs with group 1's extra barrier at loop entry
+  }
+
+  if constexpr (KS == 2) {
+    // add the second group's partial tile to the first's through LDS (the operand buffers are free:
+    // the k loop ended with a barrier)
+    float* red = reinterpret_cast<float*>(smem);     // [64 accumulators][256 threads]
+    if (grp == 1) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) red[((i * 2 + j) * 16 + e) * 256 + tid] = acc[i][j][e];
+    }
+    __syncthreads();
+    if (grp == 1) return;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * 2 + j) * 16 + e) * 256 + tid];
+  }
+
+  const int m_base = GK ? seg * TM : 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int r = wm * 64 + i * 32 + 8 * (e >> 2) + (lane >> 5) * 4 + (e & 3);
+      int64_t crow;
+      if constexpr (GK) crow = m_base + r;
+      else              crow = s_rows_c[r];
+      if (crow < 0) continue;
+      float scale = 1.f;
+      if constexpr (!GK && EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+        float v = acc[i][j][e];
+        if constexpr (EPI == EPI_GELU) v = gelu_erf(v);
+        if constexpr (EPI == EPI_STORE) v *= scale;
+        if constexpr (EPI == EPI_ATOMIC) {
+          atomicAdd(reinterpret_cast<float*>(g.C) + crow * g.ldc + col, v);
+        } else if constexpr (CT == 0) {
+          reinterpret_cast<float*>(g.C)[crow * g.ldc + col] = v;
+        } else {
+          reinterpret_cast<uint16_t*>(g.C)[crow * g.ldc + col] = f32_to_in<BF>(v);
+        }
+      }
+    }
+  }
+}
+
 // Zero rows of C that no index entry names (single-segment GATHER_M): the list is ascending, so a
 // row is uncovered iff a binary search misses it.  One wave per row, 16-byte stores.
 template <int ESIZE>
@@ -302,9 +708,32 @@ __global__ void __launch_bounds__(256) k_zero_rows(void* C, int64_t ld_bytes, in
 
 }  // namespace
 
+static int gemm_variant() {
+  static const int v = [] { const char* e = getenv("PIT_GEMM_VARIANT"); return e ? atoi(e) : 22; }();
+  return v;
+}
+
 template <bool BF, bool GK, int EPI, int CT>
 static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
-  hipLaunchKernelGGL((k_sread_gemm<BF, GK, EPI, CT>), grid, dim3(256), 0, st, g);
+  if constexpr (BF && GK && EPI == EPI_STORE && CT == 0) {
+    static const int abl = [] { const char* e = getenv("PIT_GEMM_ABL"); return e ? atoi(e) : 0; }();
+    switch (abl) {
+      case 1: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2, 1>), grid, dim3(512), 0, st, g); return PIT_OK;
+      case 2: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2, 2>), grid, dim3(512), 0, st, g); return PIT_OK;
+      case 3: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2, 3>), grid, dim3(512), 0, st, g); return PIT_OK;
+      case 4: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2, 4>), grid, dim3(512), 0, st, g); return PIT_OK;
+      case 5: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2, 5>), grid, dim3(512), 0, st, g); return PIT_OK;
+      case 6: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2, 6>), grid, dim3(512), 0, st, g); return PIT_OK;
+      case 7: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2, 7>), grid, dim3(512), 0, st, g); return PIT_OK;
+      default: break;
+    }
+  }
+  switch (gemm_variant()) {
+    case 0: hipLaunchKernelGGL((k_sread_gemm<BF, GK, EPI, CT>), grid, dim3(256), 0, st, g); break;
+    case 2: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 1>), grid, dim3(256), 0, st, g); break;
+    case 4: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 4, 1>), grid, dim3(256), 0, st, g); break;
+    default: hipLaunchKernelGGL((k_sread_gemm3<BF, GK, EPI, CT, 2, 2>), grid, dim3(512), 0, st, g); break;
+  }
   PIT_LAUNCH_CHECK();
   return PIT_OK;
 }
