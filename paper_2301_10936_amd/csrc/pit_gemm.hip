@@ -78,6 +78,20 @@ __device__ __forceinline__ uint32_t tile_off(int m, int c) {
   return (uint32_t)((((a << 3) | l) << 8) | (h << 7) | (((c ^ l ^ a) & 7) << 4));
 }
 
+// One output row of the 8 x 8 transpose below: out_x = 8 consecutive k of column x (4 v_perm_b32).
+__device__ __forceinline__ uint4 transpose8x8_row(const uint4 (&r)[8], int x) {
+  const int i = x >> 1;
+  const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+  uint32_t d[4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const uint32_t a = i == 0 ? r[2 * jj].x : i == 1 ? r[2 * jj].y : i == 2 ? r[2 * jj].z : r[2 * jj].w;
+    const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
+    d[jj] = __builtin_amdgcn_perm(b, a, sel);
+  }
+  return make_uint4(d[0], d[1], d[2], d[3]);
+}
+
 // r[j] = 8 consecutive columns of k-row j (16-bit elements); out[x] = 8 consecutive k of column x
 __device__ __forceinline__ void transpose8x8_b16(const uint4 (&r)[8], uint4 (&out)[8]) {
 #pragma unroll
@@ -281,19 +295,38 @@ k_sread_gemm(const GemmArgs g) {
       }
     }
   };
+  // byte offsets of the 8 loads of `step` (same addresses as issue())
+  auto issue_offsets = [&](int step, uint32_t (&off)[8]) {
+    if constexpr (GK) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) off[j] = __umul24((uint32_t)k_use[j], pitch) + col_bytes;
+    } else {
+      if (is_b) {
+        const int base = k_begin + min(step * TK + t_kg * 8, k_len - 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) off[j] = __umul24((uint32_t)(base + j), pitch) + col_bytes;
+      } else {
+        const uint32_t kofs = (uint32_t)((min(step * TK + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) off[j] = a_off[j] + kofs;
+      }
+    }
+  };
+  // zero what lies past the end of the k extent (last, partial step only)
+  auto zero_tail = [&](int step, uint4 (&r)[8]) {
+    if (transposing) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (step * TK + t_kg * 8 + j >= len) r[j] = make_uint4(0, 0, 0, 0);
+    } else if (step * TK + s_chunk * 8 >= len) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) r[j] = make_uint4(0, 0, 0, 0);
+    }
+  };
   // the 8 x 16 B this thread will write to LDS for `step`: transposed (or straight) and, in the
   // last partial step, with everything past the end of the k extent zeroed
   auto prepare = [&](int step, uint4 (&r)[8], uint4 (&o)[8], bool may_be_last) {
-    if (may_be_last && tail != 0 && step == nsteps - 1) {
-      if (transposing) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (step * TK + t_kg * 8 + j >= len) r[j] = make_uint4(0, 0, 0, 0);
-      } else if (step * TK + s_chunk * 8 >= len) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = make_uint4(0, 0, 0, 0);
-      }
-    }
+    if (may_be_last && tail != 0 && step == nsteps - 1) zero_tail(step, r);
     if (transposing) {
       transpose8x8_b16(r, o);
     } else {
@@ -316,27 +349,40 @@ k_sread_gemm(const GemmArgs g) {
   };
   // One step.  MFMAs of `step` read LDS buffer `buf`; the tile of step + 1, already transposed in
   // the registers o[], goes to the other buffer; the tile of step + 2 is taken out of ring slot r
-  // and transposed into o[]; the loads of step + 2 + D refill the slot.  The LDS traffic (16 reads
-  // and 8 writes per wavefront) is spread evenly over the four MFMA groups.
-  auto body = [&](int step, int buf, uint4 (&o)[8], uint4 (&r)[8], bool do_write, bool do_prep, bool do_issue, bool may_be_last) {
+  // and transposed into o[]; the loads of step + 1 + D refill ring slot rl (the one emptied by the
+  // previous step).  A wavefront issues in order and an MFMA keeps the matrix pipe busy for 32
+  // clocks, so everything else is placed BETWEEN consecutive MFMAs, about 30 clocks' worth each:
+  //   MFMA 0..7    one LDS read (operands of the next k-substep), one LDS write, one global load
+  //   MFMA 8..11   one LDS read, a quarter of the transpose (4 v_perm_b32) ... MFMA 12..15 likewise
+  // `steady` = compile-time true in the branch-free loop (all parts on, order pinned).
+  auto body = [&](int step, int buf, uint4 (&o)[8], uint4 (&r)[8], uint4 (&rl)[8],
+                  bool do_write, bool do_prep, bool do_issue, bool steady) {
     const uint32_t t = lds0 + buf * STAGE_BYTES, tw = lds0 + (buf ^ 1) * STAGE_BYTES;
     u32x4_t fa[2][2], fb[2][2];
     read_frags(t, 0, fa[0], fb[0]);
-    PIT_SCHED_FENCE();
+    if (!steady && do_prep && tail != 0 && step + 2 == nsteps - 1) zero_tail(step + 2, r);
+    uint32_t goff[8];
+    if (do_issue) issue_offsets(step + 1 + D, goff);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks < 3) read_frags(t, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-      if (do_write) {
-        lds_write_b128(tw + w_off[2 * ks], o[2 * ks]);
-        lds_write_b128(tw + w_off[2 * ks + 1], o[2 * ks + 1]);
+    for (int i = 0; i < 16; ++i) {
+      const int ks = i >> 2, q = i & 3;
+      acc[q >> 1][q & 1] = mfma32<BF>(fa[ks & 1][q >> 1], fb[ks & 1][q & 1], acc[q >> 1][q & 1]);
+      if (i < 12) {   // operands of k-substep ks + 1: A block 0, B block 0, A block 1, B block 1
+        const int nb = (ks + 1) & 1;
+        if (q == 0) fa[nb][0] = lds_read_frag(t + rd_a[0][ks + 1]);
+        if (q == 1) fb[nb][0] = lds_read_frag(t + rd_b[0][ks + 1]);
+        if (q == 2) fa[nb][1] = lds_read_frag(t + rd_a[1][ks + 1]);
+        if (q == 3) fb[nb][1] = lds_read_frag(t + rd_b[1][ks + 1]);
       }
-      mfma4(fa[ks & 1], fb[ks & 1]);
-      if (ks == 3) {
-        if (do_prep) prepare(step + 2, r, o, may_be_last);
-        if (do_issue) issue(step + 2 + D, r);
+      if (i < 8) {
+        if (do_write) lds_write_b128(tw + w_off[i], o[i]);
+        if (do_issue) rl[i] = load16(src, goff[i]);
+      } else if (do_prep) {
+        o[i - 8] = transposing ? transpose8x8_row(r, i - 8) : r[i - 8];
       }
-      PIT_SCHED_FENCE();
+      if (steady) PIT_SCHED_FENCE();   // keep the slots in this order (the scheduler would cluster the MFMAs)
     }
+    PIT_SCHED_FENCE();
     __syncthreads();
   };
 
@@ -350,18 +396,22 @@ k_sread_gemm(const GemmArgs g) {
       for (int q = 0; q < 4; ++q) s_kidx[q * 256 + tid] = v[q];
       __syncthreads();
     }
-    // prologue: loads of steps 0 .. D+1; tile 0 into LDS, tile 1 transposed into o[]
+    // prologue: loads of tiles 0 .. D; tile 0 into LDS, tile 1 transposed into o[].  Tile t >= 2
+    // travels through ring slot (t - 2) % D; slot D-1 is filled by step 0.
     uint4 o[8], r0[8], r1[8];
     if constexpr (GK) load_kid(0, k_use);
     issue(0, r0);
     if constexpr (GK) load_kid(min(1, nsteps - 1), k_use);
     issue(min(1, nsteps - 1), r1);
 #pragma unroll
-    for (int s = 0; s < D; ++s) {
+    for (int s = 0; s + 1 < D; ++s) {
       if constexpr (GK) load_kid(min(2 + s, nsteps - 1), k_use);
       issue(min(2 + s, nsteps - 1), R[s]);
     }
-    if constexpr (GK) load_kid(min(2 + D, nsteps - 1), k_pend);
+    if constexpr (GK) {
+      load_kid(min(1 + D, nsteps - 1), k_use);
+      load_kid(min(2 + D, nsteps - 1), k_pend);
+    }
     prepare(0, r0, o, true);
 #pragma unroll
     for (int x = 0; x < 8; ++x) lds_write_b128(lds0 + w_off[x], o[x]);
@@ -375,17 +425,15 @@ k_sread_gemm(const GemmArgs g) {
 #pragma unroll
       for (int uu = 0; uu < 4; ++uu) {
         const int step = it + uu;
+        body(step, uu & 1, o, R[uu % D], R[(uu + D - 1) % D], true, true, true, true);
         if constexpr (GK) {
+          // list entries for the loads of the next step, and the sliding window's refill
 #pragma unroll
           for (int j = 0; j < 8; ++j) k_use[j] = k_pend[j];
           load_kid(min(step + 3 + D, nsteps - 1), k_pend);
           if (uu == 0) k_ahead = list_at((step + 12) * TK + tid);
           if (uu == 3) s_kidx[((step + 9) * TK + tid) & (KRING - 1)] = k_ahead;   // entries of steps it+12 .. it+15
-          // the list fetch stays ahead of this step's data loads in program order: the memory
-          // counter is in-order, so waiting for it later never drains the younger data loads
-          PIT_SCHED_FENCE();
         }
-        body(step, uu & 1, o, R[uu % D], true, true, true, false);
       }
     }
     // drain
@@ -394,13 +442,12 @@ k_sread_gemm(const GemmArgs g) {
       for (int uu = 0; uu < 4; ++uu) {
         const int step = it + uu;
         if (step >= nsteps) break;
-        const bool more = step + 2 + D < nsteps;
+        body(step, uu & 1, o, R[uu % D], R[(uu + D - 1) % D], step + 1 < nsteps, step + 2 < nsteps, step + 1 + D < nsteps, false);
         if constexpr (GK) {
 #pragma unroll
           for (int j = 0; j < 8; ++j) k_use[j] = k_pend[j];
           load_kid(min(step + 3 + D, nsteps - 1), k_pend);
         }
-        body(step, uu & 1, o, R[uu % D], step + 1 < nsteps, step + 2 < nsteps, more, true);
       }
     }
   }
