@@ -300,15 +300,15 @@ def main():
         "config": {"workload": "relu_ffn_down_proj: X^T[8192 ch x 2048 tok]=ReLU(N(-1.2,1)) bf16 channel-major, "
                                "W2[8192x2048] bf16 N(0,0.02), fp32 accumulate and output; index rebuilt every step "
                                "from a pool of 8 activations; effective FLOPs counted on non-zero 32x1 micro-tiles",
-                   "M": 2048, "K": 8192, "N": 2048, "dense_tile": "128x128x64", "index_microtile": "128x1"},
+                   "M": 2048, "K": 8192, "N": 2048, "dense_tile": "128x128x32 per wave, 4-wave split of the k-list", "index_microtile": "128x1"},
         "frac_mfma_peak": round(value / MFMA_PEAK_TFLOPS, 4),
         "speedup_vs_dense": round(r["dense_ms"] / (sec * 1e3), 3),
         "dense_gemm_ms": round(r["dense_ms"], 4),
         "index_build_ms": round(r["index_ms"], 4), "gemm_ms": round(r["gemm_ms"], 4),
         "index_share_of_step": round(r["index_ms"] / (r["index_ms"] + r["gemm_ms"]), 4),
-        "roofline": {"bound": "mfma", "kernel": "k_sread_gemm (GATHER_K, bf16)", "achieved": round(gemm_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": "k_gather_k_direct (bf16)", "achieved": round(gemm_tflops, 2),
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": _read_traffic("k_sread_gemm_gather_k_relu_ffn.txt")},
+                     "traffic": _read_traffic("k_gather_k_direct_relu_ffn.txt")},
         "paper_context": "paper reports up to 5.9x (avg 2.43x) over compilers on A100/V100 end-to-end; no TFLOP/s figure",
     }
     if "cpu" in r:

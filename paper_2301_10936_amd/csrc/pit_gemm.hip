@@ -1,34 +1,32 @@
-// pit_sread_gemm: the SRead -> dense MFMA tile -> SWrite kernel (paper Section 3.1, sparse kernel
-// template) for gfx950, and its host-side validation and launch.
+// pit_sread_gemm: the SRead -> dense MFMA tile -> SWrite kernels (paper Section 3.1, sparse kernel
+// template) for gfx950, and their host-side validation and launch.
 //
-// One workgroup (256 threads = 4 wavefronts, 2 x 2) computes a 128 x 128 dense tile of C with
-// v_mfma_f32_32x32x16 (bf16 or f16 inputs, fp32 accumulation), 64 k per step.
+// A workgroup (256 threads = 4 wavefronts) computes a 128 x 128 dense tile of C with bf16 or f16
+// inputs and fp32 accumulation.  There is one kernel per PIT-axis of MatMul (paper Table 1):
 //
-// SRead.  Two gathers, one per PIT-axis of MatMul (paper Table 1):
-//   GATHER_K  A is K-major (At[k][m]); the tile's k-list comes from the index; a step loads the 64
-//             listed rows of At (128 m = 256 B each) and the SAME rows of B.
-//   GATHER_M  A is K-minor (A[m][k]); the tile's 128 row numbers come from the index once, the
-//             k loop walks a contiguous k range; B rows are contiguous.
-// Every operand tile is K-MINOR in LDS ([128 x][64 k], 128 B per row) and is read with
-// ds_read_b128.  K-major sources (rows of At and of B) are transposed in registers on the way in:
-// a thread loads an 8 k x 8 column block (8 x 16 B, one source row each), interleaves the 16-bit
-// elements with v_perm_b32 and writes 8 tile rows of 16 B.
+//   k_gather_k_direct  GATHER_K: A is K-major (At[k][m]); the tile's k-list comes from the index and
+//             names the rows of At and of B to multiply.  Operands go global -> registers directly
+//             and are transposed inside each lane; the four waves split the k-list and reduce
+//             their partial tiles through LDS at the end (details above the kernel).
+//   k_gather_m  GATHER_M: A is K-minor (A[m][k]); the tile's 128 row numbers come from the index
+//             once, the k loop walks a contiguous k range; B rows are contiguous.  Operands are
+//             staged through LDS, 2 x 2 waves of 64 x 64 with v_mfma_f32_32x32x16, 64 k per step.
 //
-// Pipeline.  Global loads run D steps ahead in a register ring.  The steady-state loop is
-// branch-free: all loads are unconditional (positions past the end of a list are clamped to its
-// last entry and zeroed on the way into LDS, in the last step only).  Inside a step the LDS reads
-// of k-substep s+1, the transposes and the LDS writes of the next tile are interleaved with the
-// MFMAs of k-substep s, so the LDS pipe and the matrix pipe work at the same time although there
-// is a single wavefront per SIMD.
-// GATHER_K keeps a sliding window of the k-list in LDS (16 steps x 64 entries).  Every 4th step each
-// thread fetches one entry 12 steps ahead and stores it 3 steps later, so no load in the loop
-// depends on a load issued less than 3 steps before it.
+// k_gather_m in detail.  Both operand tiles are K-MINOR in LDS ([128 x][64 k], 128 B per row) and
+// are read with ds_read_b128.  The K-major source (rows of B) is transposed in registers on the way
+// in: a thread loads an 8 k x 8 column block (8 x 16 B, one source row each), interleaves the 16-bit
+// elements with v_perm_b32 and writes 8 tile rows of 16 B.  Global loads run 2 steps ahead in a
+// register ring.  The steady-state loop is branch-free: all loads are unconditional (k past the end
+// of the slab is clamped and zeroed on the way into LDS, in the last step only).  Inside a step the
+// LDS reads of k-substep s+1, the transposes and the LDS writes of the next tile are interleaved
+// with the MFMAs of k-substep s, so the LDS pipe and the matrix pipe work at the same time although
+// there is a single wavefront per SIMD.
 //
-// SWrite.  The epilogue stores accumulator rows to the row numbers held in LDS (identity or the
-// index), optionally through fp32 atomics (several k-slabs accumulate into one C), a GELU + round
-// to the input type (first MoE matmul) or a per-row gate (second MoE matmul).
+// SWrite.  The GATHER_M epilogue stores accumulator rows to the row numbers held in LDS (compact or
+// from the index), optionally through fp32 atomics (several k-slabs accumulate into one C), a GELU
+// + round to the input type (first MoE matmul) or a per-row gate (second MoE matmul).  GATHER_K
+// writes the rows of its m-tile in place.
 #include "pit_gemm.hpp"
-#include <cstdlib>
 
 namespace pit {
 namespace {
@@ -78,6 +76,14 @@ __device__ __forceinline__ uint32_t tile_off(int m, int c) {
   return (uint32_t)((((a << 3) | l) << 8) | (h << 7) | (((c ^ l ^ a) & 7) << 4));
 }
 
+// Dword jj (k = 2 jj, 2 jj + 1) of column x of the 8 x 8 transpose below (one v_perm_b32).
+__device__ __forceinline__ uint32_t transpose8x8_dword(const uint4 (&r)[8], int x, int jj) {
+  const int i = x >> 1;
+  const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+  const uint32_t a = i == 0 ? r[2 * jj].x : i == 1 ? r[2 * jj].y : i == 2 ? r[2 * jj].z : r[2 * jj].w;
+  const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
+  return __builtin_amdgcn_perm(b, a, sel);
+}
 // One output row of the 8 x 8 transpose below: out_x = 8 consecutive k of column x (4 v_perm_b32).
 __device__ __forceinline__ uint4 transpose8x8_row(const uint4 (&r)[8], int x) {
   const int i = x >> 1;
@@ -126,52 +132,26 @@ __device__ __forceinline__ uint4 load16(const char* base, uint32_t byte_off) {
 // nothing may be scheduled across this point
 #define PIT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// GK = true: GATHER_K (A K-major), false: GATHER_M (A K-minor).  CT: 0 = fp32 C, 1 = C in the input type.
-// D: depth of the register ring of global loads (2 or 4 steps).
-template <bool BF, bool GK, int EPI, int CT, int D>
+// GATHER_M (A K-minor, rows gathered; B K-major, contiguous k).  CT: 0 = fp32 C, 1 = C in the input type.
+template <bool BF, int EPI, int CT>
 __global__ void __launch_bounds__(256)
-k_sread_gemm(const GemmArgs g) {
-  static_assert(D == 2 || D == 4, "ring depth must divide the unroll factor 4");
+k_gather_m(const GemmArgs g) {
+  constexpr int D = 2;   // depth of the register ring of global loads, in steps
   __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_BYTES];
   __shared__ int s_rows_a[TM];   // GATHER_M: source row of A per tile row
   __shared__ int s_rows_c[TM];   // destination row of C per tile row (-1 = skip)
-  constexpr int KRING = 16 * TK;
-  __shared__ __attribute__((aligned(32))) int s_kidx[GK ? KRING : 4];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(PIT_LDS char*)smem;
-  const uint32_t kring = (uint32_t)(uintptr_t)(PIT_LDS char*)s_kidx;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int wm = wv >> 1, wn = wv & 1;
 
   // ---------------------------------------------------------------- which tile is this workgroup?
-  int tile_row, tile_col;
-  if constexpr (GK) {
-    // XCD-aware tile order.  Workgroups are handed to the 8 XCDs round-robin by linear id, and
-    // each XCD has its own L2.  Renumber so that the workgroups of one XCD are consecutive, then
-    // walk the tile grid in bands of 4 row tiles (row-fastest inside a band): an XCD's workgroups
-    // then cover a compact block of tiles and share their A and B panels through that L2.
-    const int tn = gridDim.x, tm = gridDim.y, total = tn * tm;
-    const int lin = blockIdx.x + tn * blockIdx.y;
-    const int x = lin & 7, q = total >> 3, r = total & 7;
-    const int lp = x * q + min(x, r) + (lin >> 3);
-    constexpr int GM = 4;
-    const int band = lp / (GM * tn), within = lp - band * (GM * tn);
-    const int rows = min(GM, tm - band * GM);
-    tile_row = band * GM + within % rows;
-    tile_col = within / rows;
-  } else {
-    tile_row = blockIdx.y;
-    tile_col = blockIdx.x;
-  }
+  const int tile_row = blockIdx.y, tile_col = blockIdx.x;
   const int n0 = tile_col * TN;
 
-  int seg, list_begin, list_len;   // GATHER_K: the k-list; GATHER_M: the row-list slice of this tile
-  int k_begin = 0, k_len = 0;      // GATHER_M: contiguous k range
-  if constexpr (GK) {
-    seg = tile_row;
-    list_begin = g.seg_ptr[seg];
-    list_len = g.seg_ptr[seg + 1] - list_begin;
-  } else {
+  int seg, list_begin, list_len;   // the row-list slice of this tile
+  int k_begin = 0, k_len = 0;      // contiguous k range
+  {
     // linear row-tile number -> (segment, tile inside segment); every wave does the same search
     const int tile = tile_row;
     int acc = 0;
@@ -226,7 +206,7 @@ k_sread_gemm(const GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int len = GK ? list_len : k_len;          // extent of the k loop (list entries or slab width)
+  const int len = k_len;                           // extent of the k loop (slab width)
   const int nsteps = (len + TK - 1) / TK;
   const int tail = len % TK;                       // != 0: the last step is partial
 
@@ -234,21 +214,19 @@ k_sread_gemm(const GemmArgs g) {
   const bool is_b = __builtin_amdgcn_readfirstlane(tid >> 7) != 0;
   const int u = tid & 127;
   const int t_cg = u & 15, t_kg = u >> 4;                               // transposing role: 8 k x 8 columns
-  const int s_chunk = u & 7, s_row = (((u >> 3) & 1) << 3) | (u >> 4);  // straight role (GATHER_M, A): rows r, r+8 per 16 lanes
-  const bool transposing = GK || is_b;
+  const int s_chunk = u & 7, s_row = (((u >> 3) & 1) << 3) | (u >> 4);  // straight role (A): rows r, r+8 per 16 lanes
+  const bool transposing = is_b;
 
   const char* a_bytes = reinterpret_cast<const char*>(g.A);
   const char* b_bytes = reinterpret_cast<const char*>(g.B) + (int64_t)seg * g.b_seg_stride * 2;
   const char* src = uniform_ptr(is_b ? b_bytes : a_bytes);
   const uint32_t pitch = (uint32_t)((is_b ? g.ldb : g.lda) * 2);   // bytes per source row (< 2^24, checked on the host)
   // transposing role: byte offset of this thread's 8 columns inside a source row
-  const uint32_t col_bytes = (uint32_t)(((GK && !is_b) ? seg * TM : n0) + t_cg * 8) * 2u;
+  const uint32_t col_bytes = (uint32_t)(n0 + t_cg * 8) * 2u;
 
   uint32_t a_off[8];   // straight role: byte offset of (row of round j, this thread's chunk) at k step 0
-  if constexpr (!GK) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a_off[j] = __umul24((uint32_t)s_rows_a[j * 16 + s_row], pitch) + (uint32_t)(k_begin + s_chunk * 8) * 2u;
-  }
+  for (int j = 0; j < 8; ++j) a_off[j] = __umul24((uint32_t)s_rows_a[j * 16 + s_row], pitch) + (uint32_t)(k_begin + s_chunk * 8) * 2u;
 
   // LDS write offsets (8 per thread) and read offsets (32-row block i of this wave, k-substep ks)
   uint32_t w_off[8];
@@ -267,49 +245,29 @@ k_sread_gemm(const GemmArgs g) {
   }
 
   uint4 R[D][8];
-  int k_use[8], k_pend[8];   // GATHER_K: list values for the step being issued / the one after
-  int k_ahead = 0;           // GATHER_K: one list entry on its way from global memory to the LDS window
 
-  auto list_at = [&](int pos) { return g.idx[list_begin + min(pos, list_len - 1)]; };
-  auto load_kid = [&](int step, int (&dst)[8]) {
-    const uint32_t a = kring + (uint32_t)((((step & 15) << 6) + t_kg * 8) * 4);
-    const u32x4_t lo = *(PIT_LDS u32x4_t*)(uintptr_t)a;
-    const u32x4_t hi = *(PIT_LDS u32x4_t*)(uintptr_t)(a + 16);
-    dst[0] = lo.x; dst[1] = lo.y; dst[2] = lo.z; dst[3] = lo.w;
-    dst[4] = hi.x; dst[5] = hi.y; dst[6] = hi.z; dst[7] = hi.w;
-  };
   auto issue = [&](int step, uint4 (&r)[8]) {
-    if constexpr (GK) {
+    if (is_b) {
+      const int base = k_begin + min(step * TK + t_kg * 8, k_len - 8);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) r[j] = load16(src, __umul24((uint32_t)k_use[j], pitch) + col_bytes);
+      for (int j = 0; j < 8; ++j) r[j] = load16(src, __umul24((uint32_t)(base + j), pitch) + col_bytes);
     } else {
-      if (is_b) {
-        const int base = k_begin + min(step * TK + t_kg * 8, k_len - 8);
+      // byte distance from this thread's chunk at step 0; a chunk past the slab end re-reads the last one
+      const uint32_t kofs = (uint32_t)((min(step * TK + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = load16(src, __umul24((uint32_t)(base + j), pitch) + col_bytes);
-      } else {
-        // byte distance from this thread's chunk at step 0; a chunk past the slab end re-reads the last one
-        const uint32_t kofs = (uint32_t)((min(step * TK + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) r[j] = load16(src, a_off[j] + kofs);
-      }
+      for (int j = 0; j < 8; ++j) r[j] = load16(src, a_off[j] + kofs);
     }
   };
   // byte offsets of the 8 loads of `step` (same addresses as issue())
   auto issue_offsets = [&](int step, uint32_t (&off)[8]) {
-    if constexpr (GK) {
+    if (is_b) {
+      const int base = k_begin + min(step * TK + t_kg * 8, k_len - 8);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) off[j] = __umul24((uint32_t)k_use[j], pitch) + col_bytes;
+      for (int j = 0; j < 8; ++j) off[j] = __umul24((uint32_t)(base + j), pitch) + col_bytes;
     } else {
-      if (is_b) {
-        const int base = k_begin + min(step * TK + t_kg * 8, k_len - 8);
+      const uint32_t kofs = (uint32_t)((min(step * TK + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) off[j] = __umul24((uint32_t)(base + j), pitch) + col_bytes;
-      } else {
-        const uint32_t kofs = (uint32_t)((min(step * TK + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) off[j] = a_off[j] + kofs;
-      }
+      for (int j = 0; j < 8; ++j) off[j] = a_off[j] + kofs;
     }
   };
   // zero what lies past the end of the k extent (last, partial step only)
@@ -387,31 +345,13 @@ k_sread_gemm(const GemmArgs g) {
   };
 
   if (nsteps > 0) {
-    if constexpr (GK) {
-      // list window for steps 0..15
-      int v[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) v[q] = list_at(q * 256 + tid);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) s_kidx[q * 256 + tid] = v[q];
-      __syncthreads();
-    }
     // prologue: loads of tiles 0 .. D; tile 0 into LDS, tile 1 transposed into o[].  Tile t >= 2
     // travels through ring slot (t - 2) % D; slot D-1 is filled by step 0.
     uint4 o[8], r0[8], r1[8];
-    if constexpr (GK) load_kid(0, k_use);
     issue(0, r0);
-    if constexpr (GK) load_kid(min(1, nsteps - 1), k_use);
     issue(min(1, nsteps - 1), r1);
 #pragma unroll
-    for (int s = 0; s + 1 < D; ++s) {
-      if constexpr (GK) load_kid(min(2 + s, nsteps - 1), k_use);
-      issue(min(2 + s, nsteps - 1), R[s]);
-    }
-    if constexpr (GK) {
-      load_kid(min(1 + D, nsteps - 1), k_use);
-      load_kid(min(2 + D, nsteps - 1), k_pend);
-    }
+    for (int s = 0; s + 1 < D; ++s) issue(min(2 + s, nsteps - 1), R[s]);
     prepare(0, r0, o, true);
 #pragma unroll
     for (int x = 0; x < 8; ++x) lds_write_b128(lds0 + w_off[x], o[x]);
@@ -423,18 +363,8 @@ k_sread_gemm(const GemmArgs g) {
     // around memory operations
     for (; it + 5 + D < nsteps; it += 4) {
 #pragma unroll
-      for (int uu = 0; uu < 4; ++uu) {
-        const int step = it + uu;
-        body(step, uu & 1, o, R[uu % D], R[(uu + D - 1) % D], true, true, true, true);
-        if constexpr (GK) {
-          // list entries for the loads of the next step, and the sliding window's refill
-#pragma unroll
-          for (int j = 0; j < 8; ++j) k_use[j] = k_pend[j];
-          load_kid(min(step + 3 + D, nsteps - 1), k_pend);
-          if (uu == 0) k_ahead = list_at((step + 12) * TK + tid);
-          if (uu == 3) s_kidx[((step + 9) * TK + tid) & (KRING - 1)] = k_ahead;   // entries of steps it+12 .. it+15
-        }
-      }
+      for (int uu = 0; uu < 4; ++uu)
+        body(it + uu, uu & 1, o, R[uu % D], R[(uu + D - 1) % D], true, true, true, true);
     }
     // drain
     for (; it < nsteps; it += 4) {
@@ -443,28 +373,20 @@ k_sread_gemm(const GemmArgs g) {
         const int step = it + uu;
         if (step >= nsteps) break;
         body(step, uu & 1, o, R[uu % D], R[(uu + D - 1) % D], step + 1 < nsteps, step + 2 < nsteps, step + 1 + D < nsteps, false);
-        if constexpr (GK) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) k_use[j] = k_pend[j];
-          load_kid(min(step + 3 + D, nsteps - 1), k_pend);
-        }
       }
     }
   }
 
   // ---------------------------------------------------------------- SWrite
-  const int m_base = GK ? seg * TM : 0;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int r = wm * 64 + i * 32 + 8 * (e >> 2) + (lane >> 5) * 4 + (e & 3);
-      int64_t crow;
-      if constexpr (GK) crow = m_base + r;
-      else              crow = s_rows_c[r];
+      const int64_t crow = s_rows_c[r];
       if (crow < 0) continue;
       float scale = 1.f;
-      if constexpr (!GK && EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
+      if constexpr (EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int col = n0 + wn * 64 + j * 32 + (lane & 31);
@@ -481,6 +403,229 @@ k_sread_gemm(const GemmArgs g) {
       }
     }
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// GATHER_K, register-direct: no LDS and no barrier inside the k loop.
+//
+// Both operands of GATHER_K are K-major (rows of At and of B), and an MFMA operand register holds
+// 8 consecutive k of ONE column.  A lane that loads 16 bytes (8 columns) from each of 8 listed
+// rows owns an 8 k x 8 column block, and transposing that block inside the lane (v_perm_b32, no
+// cross-lane traffic) yields 8 operand registers, one per column.  With v_mfma_f32_16x16x32 (lane
+// l: column l % 16, k-block l / 16) 16 lanes x 8 columns cover 128 columns, so a wavefront's 8
+// loads of At give it the A operands of all 128 tile rows for 32 k, its 8 loads of B the B
+// operands of all 128 tile columns, and 8 x 8 MFMAs consume them: MFMA (ja, jb) works on the
+// strided row set {8r + ja} and column set {8c + jb}.  Each operand byte travels global -> register
+// exactly once per workgroup and never through LDS.
+// The four wavefronts split the tile's k-list in slabs of 32 entries (wave w takes slabs w, w+4, ..),
+// each accumulating a full 128 x 128 partial tile in 256 accumulator registers; at the end the
+// partial tiles are reduce-scattered through LDS (3 rounds of 64 KiB) and every wave stores a
+// quarter of the tile, 512 contiguous bytes per row.
+// The k loop is branch-free: list positions past the end are clamped to the last entry on load, the
+// last slab of each wave is processed apart with the clamped rows zeroed.
+// ------------------------------------------------------------------------------------------------
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// acc += A * B with v_mfma_f32_16x16x32.  Written as inline assembly so that the accumulator is
+// updated IN PLACE in an accumulation register: with all 256 of them live the register allocator
+// otherwise gives the result a different register than the input and shuffles accumulators
+// through vector registers between MFMAs.  The assembly is opaque to the compiler's hazard
+// handling: callers must leave 64 other MFMAs (or PIT_MFMA_DRAIN) between an update of an
+// accumulator and its next use.
+template <bool BF>
+__device__ __forceinline__ void mfma16_acc(const uint4& a, const uint4& b, f32x4_t& c) {
+  const u32x4_t av = __builtin_bit_cast(u32x4_t, a), bv = __builtin_bit_cast(u32x4_t, b);
+  if constexpr (BF) asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(av), "v"(bv));
+  else              asm("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(av), "v"(bv));
+}
+// wait until the matrix pipe has written every accumulator (a 4-pass MFMA needs at most 10 idle
+// issue slots before another kind of instruction may read its result)
+#define PIT_MFMA_DRAIN() do { PIT_SCHED_FENCE(); asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); PIT_SCHED_FENCE(); } while (0)
+
+constexpr int RED_SLOT_BYTES = 16 * 64 * 16;        // 16 accumulator quads x 64 lanes x 16 B
+constexpr int RED_BUF_BYTES = 4 * RED_SLOT_BYTES;   // one slot per sending wave
+
+// Round P of the reduction: the partial sums of tile rows {8r + ja : ja in {2P, 2P + 1}} go to wave
+// P.  P is a compile-time constant so that every accumulator index is static.
+template <int P>
+__device__ __forceinline__ void red_send(const f32x4_t (&acc)[8][8], PIT_LDS char* buf, int wv, int lane) {
+  PIT_LDS char* slot = buf + wv * RED_SLOT_BYTES + lane * 16;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int jb = 0; jb < 8; ++jb) *(PIT_LDS f32x4_t*)(slot + (a * 8 + jb) * 1024) = acc[2 * P + a][jb];
+}
+// Wave P adds the three other waves' partial sums and stores its quarter of the tile: rows
+// 32 * (lane / 16) + 8 e + ja; a lane holds 8 consecutive columns of such a row (one per jb), so 16
+// lanes write 512 (fp32) or 256 contiguous bytes.
+template <bool BF, int CT, int P>
+__device__ __forceinline__ void red_recv_store(f32x4_t (&acc)[8][8], PIT_LDS char* buf, const GemmArgs& g,
+                                               int m_base, int n0, int lane) {
+#pragma unroll
+  for (int o = 1; o < 4; ++o) {
+    PIT_LDS char* slot = buf + ((P + o) & 3) * RED_SLOT_BYTES + lane * 16;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int jb = 0; jb < 8; ++jb) acc[2 * P + a][jb] += *(PIT_LDS f32x4_t*)(slot + (a * 8 + jb) * 1024);
+  }
+  const int q = lane & 15, kb = lane >> 4;
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int ja = 2 * P + a;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int64_t row = m_base + 32 * kb + 8 * e + ja;
+      const int col = n0 + 8 * q;
+      if constexpr (CT == 0) {
+        float* d = reinterpret_cast<float*>(g.C) + row * g.ldc + col;
+        *reinterpret_cast<float4*>(d)     = make_float4(acc[ja][0][e], acc[ja][1][e], acc[ja][2][e], acc[ja][3][e]);
+        *reinterpret_cast<float4*>(d + 4) = make_float4(acc[ja][4][e], acc[ja][5][e], acc[ja][6][e], acc[ja][7][e]);
+      } else {
+        uint32_t w[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+          w[x] = (uint32_t)f32_to_in<BF>(acc[ja][2 * x][e]) | ((uint32_t)f32_to_in<BF>(acc[ja][2 * x + 1][e]) << 16);
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(g.C) + row * g.ldc + col) = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+    }
+  }
+}
+
+template <bool BF, int CT>
+__global__ void __launch_bounds__(256)
+k_gather_k_direct(const GemmArgs g) {
+  constexpr int SK = 32;   // list entries per slab = k extent of one MFMA
+  __shared__ __attribute__((aligned(16))) char s_red[2 * RED_BUF_BYTES];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that each
+  // XCD works on a contiguous run of tiles, ordered in bands of 4 tile rows x all tile columns.
+  int tile_row, tile_col;
+  {
+    const int tn = gridDim.x, tm = gridDim.y, total = tn * tm;
+    const int lin = blockIdx.x + tn * blockIdx.y;
+    const int x = lin & 7, qq = total >> 3, rr = total & 7;
+    const int lp = x * qq + min(x, rr) + (lin >> 3);
+    constexpr int GM = 4;
+    const int band = lp / (GM * tn), within = lp - band * (GM * tn);
+    const int rows = min(GM, tm - band * GM);
+    tile_row = band * GM + within % rows;
+    tile_col = within / rows;
+  }
+  const int n0 = tile_col * TN;
+  const int seg = tile_row;
+  const int list_begin = g.seg_ptr[seg];
+  const int list_len = g.seg_ptr[seg + 1] - list_begin;
+  const int nslab = (list_len + SK - 1) / SK;
+  const int n_w = nslab > wv ? (nslab - wv + 3) >> 2 : 0;   // this wave's slabs: wv, wv + 4, ...
+
+  f32x4_t acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int q = lane & 15, kb = lane >> 4;
+  const char* a_src = uniform_ptr(g.A);
+  const char* b_src = uniform_ptr(g.B);
+  const char* list = uniform_ptr(g.idx + list_begin);
+  const uint32_t pitch_a = (uint32_t)(g.lda * 2), pitch_b = (uint32_t)(g.ldb * 2);
+  const uint32_t a_col = (uint32_t)(seg * TM + 8 * q) * 2u, b_col = (uint32_t)(n0 + 8 * q) * 2u;
+
+  // lane l of a slab's list load holds entry (l % 32) of the slab
+  auto load_list = [&](int t) -> int {
+    const int pos = min(SK * (wv + 4 * t) + (lane & 31), list_len - 1);
+    typedef const int __attribute__((address_space(1))) * gint_t;
+    return *(gint_t)(uintptr_t)(reinterpret_cast<uintptr_t>(list) + (uint32_t)pos * 4u);
+  };
+  // rows k(8 kb + i), i = 0..7, of At and of B
+  auto issue = [&](int kraw, uint4 (&ra)[8], uint4 (&rb)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t k = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * kb + i) * 4, kraw);
+      ra[i] = load16(a_src, __umul24(k, pitch_a) + a_col);
+      rb[i] = load16(b_src, __umul24(k, pitch_b) + b_col);
+    }
+  };
+  // 64 MFMAs on one slab.  All B operands are transposed first; the A operand of column group
+  // ja + 1 is transposed (4 v_perm_b32) in the shadow of the first MFMAs of group ja.  The order is
+  // pinned: an MFMA must not read a register in the issue slot right after a vector instruction
+  // wrote it, and the inline-assembly MFMAs are invisible to the compiler's hazard handling, so
+  // every operand is produced at least four MFMAs (or the explicit s_nop) before its first use.
+  auto process = [&](const uint4 (&ra)[8], const uint4 (&rb)[8]) {
+    uint4 bfr[8];
+#pragma unroll
+    for (int jb = 0; jb < 8; ++jb) bfr[jb] = transpose8x8_row(rb, jb);
+    uint32_t af[4], afn[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) af[jj] = transpose8x8_dword(ra, 0, jj);
+    PIT_SCHED_FENCE();
+    asm volatile("s_nop 3");
+    PIT_SCHED_FENCE();
+#pragma unroll
+    for (int ja = 0; ja < 8; ++ja) {
+#pragma unroll
+      for (int jb = 0; jb < 8; ++jb) {
+        mfma16_acc<BF>(make_uint4(af[0], af[1], af[2], af[3]), bfr[jb], acc[ja][jb]);
+        if (ja < 7 && jb < 4) afn[jb] = transpose8x8_dword(ra, ja + 1, jb);
+        PIT_SCHED_FENCE();
+      }
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) af[jj] = afn[jj];
+    }
+  };
+  // local slab t with the rows of positions past the end of the list zeroed
+  auto process_last = [&](int t, uint4 (&ra)[8], uint4 (&rb)[8]) {
+    const int p0 = SK * (wv + 4 * t) + 8 * kb;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (p0 + i >= list_len) { ra[i] = make_uint4(0, 0, 0, 0); rb[i] = make_uint4(0, 0, 0, 0); }
+    process(ra, rb);
+  };
+
+  if (n_w > 0) {
+    uint4 ra0[8], rb0[8], ra1[8], rb1[8];
+    // (the fences keep the list loads of slabs 2 and 3 ahead of the second slab's data loads: the
+    // memory counter retires in order, so a list load issued last would make the loop wait for all)
+    int k0 = load_list(0), k1 = load_list(1);
+    PIT_SCHED_FENCE();
+    issue(k0, ra0, rb0); k0 = load_list(2); PIT_SCHED_FENCE();
+    issue(k1, ra1, rb1); k1 = load_list(3); PIT_SCHED_FENCE();
+    int t = 0;
+    for (; t + 2 < n_w; t += 2) {
+      process(ra0, rb0); PIT_SCHED_FENCE(); issue(k0, ra0, rb0); k0 = load_list(t + 4); PIT_SCHED_FENCE();
+      process(ra1, rb1); PIT_SCHED_FENCE(); issue(k1, ra1, rb1); k1 = load_list(t + 5); PIT_SCHED_FENCE();
+    }
+    if (n_w - t == 2) {
+      process(ra0, rb0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { ra0[i] = ra1[i]; rb0[i] = rb1[i]; }
+      ++t;
+    }
+    process_last(t, ra0, rb0);
+    PIT_MFMA_DRAIN();
+  }
+
+  // Reduction across the four waves, one quarter of the tile rows per round, double-buffered in
+  // LDS: round P's partial sums are written before barrier P and read by wave P after it, while the
+  // other waves already write round P + 1 into the other buffer.
+  PIT_LDS char* red = (PIT_LDS char*)s_red;
+  const int m_base = seg * TM;
+  if (wv != 0) red_send<0>(acc, red, wv, lane);
+  __syncthreads();
+  if (wv == 0) red_recv_store<BF, CT, 0>(acc, red, g, m_base, n0, lane);
+  if (wv != 1) red_send<1>(acc, red + RED_BUF_BYTES, wv, lane);
+  __syncthreads();
+  if (wv == 1) red_recv_store<BF, CT, 1>(acc, red + RED_BUF_BYTES, g, m_base, n0, lane);
+  if (wv != 2) red_send<2>(acc, red, wv, lane);
+  __syncthreads();
+  if (wv == 2) red_recv_store<BF, CT, 2>(acc, red, g, m_base, n0, lane);
+  if (wv != 3) red_send<3>(acc, red + RED_BUF_BYTES, wv, lane);
+  __syncthreads();
+  if (wv == 3) red_recv_store<BF, CT, 3>(acc, red + RED_BUF_BYTES, g, m_base, n0, lane);
 }
 
 // Zero rows of C that no index entry names (single-segment GATHER_M): the list is ascending, so a
@@ -515,17 +660,18 @@ __global__ void __launch_bounds__(256) k_zero_rows(void* C, int64_t ld_bytes, in
 
 }  // namespace
 
-static int gemm_ring_depth() {
-  static const int v = [] { const char* e = getenv("PIT_GEMM_RING"); return e ? atoi(e) : 2; }();
-  return v == 4 ? 4 : 2;
-}
-
 template <bool BF, bool GK, int EPI, int CT>
 static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
-  if (gemm_ring_depth() == 4) hipLaunchKernelGGL((k_sread_gemm<BF, GK, EPI, CT, 4>), grid, dim3(256), 0, st, g);
-  else                        hipLaunchKernelGGL((k_sread_gemm<BF, GK, EPI, CT, 2>), grid, dim3(256), 0, st, g);
-  PIT_LAUNCH_CHECK();
-  return PIT_OK;
+  if constexpr (GK) {
+    static_assert(EPI == EPI_STORE, "GATHER_K has the plain store epilogue only");
+    hipLaunchKernelGGL((k_gather_k_direct<BF, CT>), grid, dim3(256), 0, st, g);
+    PIT_LAUNCH_CHECK();
+    return PIT_OK;
+  } else {
+    hipLaunchKernelGGL((k_gather_m<BF, EPI, CT>), grid, dim3(256), 0, st, g);
+    PIT_LAUNCH_CHECK();
+    return PIT_OK;
+  }
 }
 
 template <bool BF>
