@@ -27,6 +27,7 @@
 // + round to the input type (first MoE matmul) or a per-row gate (second MoE matmul).  GATHER_K
 // writes the rows of its m-tile in place.
 #include "pit_gemm.hpp"
+#include <type_traits>
 
 namespace pit {
 namespace {
@@ -555,13 +556,24 @@ k_gather_k_direct(const GemmArgs g) {
   // pinned: an MFMA must not read a register in the issue slot right after a vector instruction
   // wrote it, and the inline-assembly MFMAs are invisible to the compiler's hazard handling, so
   // every operand is produced at least four MFMAs (or the explicit s_nop) before its first use.
-  auto process = [&](const uint4 (&ra)[8], const uint4 (&rb)[8]) {
+  // ISSUE: the loads of the slab two ahead (list entries in kraw) are issued from inside the MFMA
+  // sequence as soon as their registers are free: the B rows during column groups 0..3 (rb is dead
+  // once the B operands are transposed), the A rows during group 7 (ra is dead once the last A
+  // operand is transposed).  Spreading them keeps 16 to 24 loads of a wave in flight; with 32 in
+  // flight at once the load path of a CU runs at less than half its rate (measured).
+  auto process_impl = [&](uint4 (&ra)[8], uint4 (&rb)[8], int kraw, auto issue_tag) {
+    constexpr bool ISSUE = decltype(issue_tag)::value;
     uint4 bfr[8];
 #pragma unroll
     for (int jb = 0; jb < 8; ++jb) bfr[jb] = transpose8x8_row(rb, jb);
     uint32_t af[4], afn[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) af[jj] = transpose8x8_dword(ra, 0, jj);
+    uint32_t kk[8];
+    if constexpr (ISSUE) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) kk[i] = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * kb + i) * 4, kraw);
+    }
     PIT_SCHED_FENCE();
     asm volatile("s_nop 3");
     PIT_SCHED_FENCE();
@@ -571,12 +583,21 @@ k_gather_k_direct(const GemmArgs g) {
       for (int jb = 0; jb < 8; ++jb) {
         mfma16_acc<BF>(make_uint4(af[0], af[1], af[2], af[3]), bfr[jb], acc[ja][jb]);
         if (ja < 7 && jb < 4) afn[jb] = transpose8x8_dword(ra, ja + 1, jb);
+        if constexpr (ISSUE) {
+          if (ja < 4 && (jb == 4 || jb == 6)) {
+            const int i = ja * 2 + ((jb - 4) >> 1);
+            rb[i] = load16(b_src, __umul24(kk[i], pitch_b) + b_col);
+          }
+          if (ja == 7) ra[jb] = load16(a_src, __umul24(kk[jb], pitch_a) + a_col);
+        }
         PIT_SCHED_FENCE();
       }
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) af[jj] = afn[jj];
     }
   };
+  auto process = [&](uint4 (&ra)[8], uint4 (&rb)[8]) { process_impl(ra, rb, 0, std::false_type{}); };
+  auto process_issue = [&](uint4 (&ra)[8], uint4 (&rb)[8], int kraw) { process_impl(ra, rb, kraw, std::true_type{}); };
   // local slab t with the rows of positions past the end of the list zeroed
   auto process_last = [&](int t, uint4 (&ra)[8], uint4 (&rb)[8]) {
     const int p0 = SK * (wv + 4 * t) + 8 * kb;
@@ -596,8 +617,8 @@ k_gather_k_direct(const GemmArgs g) {
     issue(k1, ra1, rb1); k1 = load_list(3); PIT_SCHED_FENCE();
     int t = 0;
     for (; t + 2 < n_w; t += 2) {
-      process(ra0, rb0); PIT_SCHED_FENCE(); issue(k0, ra0, rb0); k0 = load_list(t + 4); PIT_SCHED_FENCE();
-      process(ra1, rb1); PIT_SCHED_FENCE(); issue(k1, ra1, rb1); k1 = load_list(t + 5); PIT_SCHED_FENCE();
+      process_issue(ra0, rb0, k0); k0 = load_list(t + 4); PIT_SCHED_FENCE();
+      process_issue(ra1, rb1, k1); k1 = load_list(t + 5); PIT_SCHED_FENCE();
     }
     if (n_w - t == 2) {
       process(ra0, rb0);
