@@ -269,6 +269,71 @@ k_emit(const u64* __restrict__ words, const int32_t* __restrict__ seg_cnt, const
   }
 }
 
+// Same result with more workgroups, for segments of up to 1024 words (65 536 micro-tiles): one
+// workgroup per chunk of 16 words.  The chunk's own words are requested before the words that are
+// only counted, so the kernel has a single round trip to memory ahead of its stores.
+constexpr int EMIT_CH = 16;
+
+__global__ void __launch_bounds__(256)
+k_emit_chunked(const u64* __restrict__ words, const int32_t* __restrict__ seg_cnt, const uint32_t* __restrict__ occ,
+               int nseg, int npit, int W, int cap, int total_items,
+               int32_t* __restrict__ seg_ptr, int32_t* __restrict__ idx, uint32_t* __restrict__ bits,
+               int32_t* __restrict__ status) {
+  __shared__ int red[4];
+  __shared__ int wsum[4];
+  const int c = blockIdx.x, s = blockIdx.y;
+  const int tid = threadIdx.x, wv = tid >> 6, ln = lane_id();
+  const int w_first = c * EMIT_CH;
+  const int64_t row0 = (int64_t)s * W;
+
+  // wave wv emits words w_first + 4 wv .. + 3 (every lane holds all four)
+  u64 mine[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int w = w_first + wv * 4 + i;
+    mine[i] = w < W ? words[row0 + w] : 0ull;
+  }
+  // set bits ahead of this chunk: earlier segments, then the earlier words of this segment
+  int part = 0;
+  if (seg_cnt) {
+    for (int i = tid; i < s; i += 256) part += seg_cnt[i];
+    for (int i = tid; i < w_first; i += 256) part += __popcll(words[row0 + i]);
+  } else {
+    const int64_t n = row0 + w_first;
+    for (int64_t i = tid; i < n; i += 256) part += __popcll(words[i]);
+  }
+  const int base = block_sum_256(part, red);
+
+  int pc[4], wave_total = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { pc[i] = __popcll(mine[i]); wave_total += pc[i]; }
+  if (ln == 0) wsum[wv] = wave_total;
+  __syncthreads();
+  int off = base;
+  for (int i = 0; i < wv; ++i) off += wsum[i];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const u64 x = mine[i];
+    if ((x >> ln) & 1ull) {
+      const int pos = off + __popcll(x & ((1ull << ln) - 1ull));
+      const int coord = (w_first + wv * 4 + i) * 64 + ln;
+      if (pos < cap) {
+        idx[pos] = coord;
+        if (bits) bits[pos] = occ[(int64_t)s * npit + coord];
+      }
+    }
+    off += pc[i];
+  }
+  if (tid == 0) {
+    if (c == 0) seg_ptr[s] = base;
+    if (s == nseg - 1 && c == (int)gridDim.x - 1) {
+      const int total = base + wsum[0] + wsum[1] + wsum[2] + wsum[3];
+      seg_ptr[nseg] = total;
+      if (status) *status = total_items - total;
+    }
+  }
+}
+
 __global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -291,8 +356,11 @@ Layout make_layout(int rows, int cols, int mt_rows, int mt_cols, int pit_dim, in
   return L;
 }
 
-// many earlier words per segment start => precompute per-segment counts in a separate launch
-inline bool use_seg_count(const Layout& L) { return (int64_t)L.nseg * L.W > 65536; }
+// k_emit_chunked serves segments of up to 1024 words (segment number in the grid's y), k_emit (one
+// workgroup per segment) the rest.
+inline bool use_chunked_emit(const Layout& L) { return L.W <= 1024 && L.nseg <= 65535; }
+// many earlier words per workgroup => precompute per-segment counts in a separate launch
+inline bool use_seg_count(const Layout& L) { return (int64_t)L.nseg * L.W > (use_chunked_emit(L) ? 16384 : 65536); }
 
 int launch_emit(const Layout& L, const u64* words, int32_t* cnt, const uint32_t* occ, const pit_index* out,
                 int total_items, int32_t* status, hipStream_t st) {
@@ -312,8 +380,14 @@ int launch_emit(const Layout& L, const u64* words, int32_t* cnt, const uint32_t*
     PIT_LAUNCH_CHECK();
     cnt_arg = cnt;
   }
-  hipLaunchKernelGGL(k_emit, dim3(L.nseg), dim3(256), 0, st, words, cnt_arg, occ, L.nseg, L.npit, L.W, out->cap,
-                     total_items, out->seg_ptr, out->idx, out->bits, status);
+  if (use_chunked_emit(L)) {
+    hipLaunchKernelGGL(k_emit_chunked, dim3((unsigned)ceil_div(L.W, EMIT_CH), (unsigned)L.nseg), dim3(256), 0, st,
+                       words, cnt_arg, occ, L.nseg, L.npit, L.W, out->cap, total_items, out->seg_ptr, out->idx,
+                       out->bits, status);
+  } else {
+    hipLaunchKernelGGL(k_emit, dim3(L.nseg), dim3(256), 0, st, words, cnt_arg, occ, L.nseg, L.npit, L.W, out->cap,
+                       total_items, out->seg_ptr, out->idx, out->bits, status);
+  }
   PIT_LAUNCH_CHECK();
   return PIT_OK;
 }
