@@ -81,6 +81,56 @@ def test_gather_k_bf16_output(pit):
     assert fro < 3e-3   # bf16 storage alone costs ~1.7e-3; reported, the fp32 path carries the 1e-3 gate
 
 
+@pytest.mark.parametrize("live", [1, 2, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 160, 161, 255, 257])
+def test_gather_k_list_lengths_around_slab_boundaries(pit, live):
+    """The four waves split the k-list in slabs of 32: lengths that leave waves without work, with
+    one slab, with a partial last slab, with an odd and an even number of slabs."""
+    g = np.random.default_rng(1000 + live)
+    K, M, N = 300, 256, 128
+    Xt = np.zeros((K, M), dtype=np.float32)
+    rows_a = np.sort(g.choice(K, size=live, replace=False))
+    rows_b = np.sort(g.choice(K, size=min(K, live + 7), replace=False))   # second m-tile: another length
+    Xt[rows_a, :128] = g.integers(-3, 4, size=(live, 128))
+    Xt[rows_b, 128:] = g.integers(-3, 4, size=(len(rows_b), 128))
+    Xt[rows_a[0], 0] = 1.0                                                # keep the listed rows non-zero
+    Xt[rows_b[0], 128] = 1.0
+    W = g.integers(-3, 4, size=(K, N)).astype(np.float32)
+    xb, wb = wl.to_bf16_bits(Xt), wl.to_bf16_bits(W)
+    tX, tW = to_dev(xb), to_dev(wb)
+    ix = pit.pit_build_index(tX, 1, 128, 0)
+    C = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K)
+    torch.cuda.synchronize()
+    assert_index_equal(ix, orc.build_index(xb, 1, 128, 0))
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(xb, wb))
+
+
+def test_gather_k_strided_operands_and_large_last_row(pit):
+    """Row pitches larger than the row length (views into wider buffers); the last listed row holds
+    the largest finite bf16 values: positions past the end of the list re-read that row and must
+    contribute nothing (and no Inf - Inf)."""
+    g = np.random.default_rng(77)
+    K, M, N = 203, 256, 256
+    Xt = (g.integers(-2, 3, size=(K, M)) * (g.random((K, M)) < 0.3)).astype(np.float32)
+    Xt[K - 1, :] = 3.0e38
+    W = g.integers(-2, 3, size=(K, N)).astype(np.float32)
+    W[K - 1, :] = 1.0
+    xb, wb = wl.to_bf16_bits(Xt), wl.to_bf16_bits(W)
+    bigX = torch.zeros((K, M + 64), dtype=torch.bfloat16, device=dev())
+    bigW = torch.zeros((K, N + 128), dtype=torch.bfloat16, device=dev())
+    bigX[:, :M] = to_dev(xb)
+    bigW[:, :N] = to_dev(wb)
+    tX, tW = bigX[:, :M], bigW[:, :N]
+    outbuf = torch.full((M, N + 32), 9.0, device=dev())
+    ix = pit.pit_build_index(tX, 1, 128, 0)
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K, out=outbuf[:, :N])
+    torch.cuda.synchronize()
+    ref = orc.gemm_at(xb, wb)
+    got = outbuf[:, :N].cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert_close(outbuf[:, :N], ref, "strided, large last row")
+    assert torch.all(outbuf[:, N:] == 9.0)     # nothing written outside the N columns
+
+
 def test_c2_full_size(pit):
     w = wl.relu_ffn()
     C = _run_gather_k(pit, w)
