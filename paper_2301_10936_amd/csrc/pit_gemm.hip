@@ -58,10 +58,9 @@ __device__ __forceinline__ uint16_t f32_to_f16_rne(float f) {
 template <bool BF> __device__ __forceinline__ uint16_t f32_to_in(float f) {
   return BF ? f32_to_bf16_rne(f) : f32_to_f16_rne(f);
 }
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
-// The same function with erf from the rational approximation 7.1.26 of Abramowitz & Stegun
+// GELU(x) = x (1 + erf(x / sqrt 2)) / 2 with erf from the rational approximation 7.1.26 of Abramowitz & Stegun
 // (|error| <= 1.5e-7, far below the rounding of the result to bf16 / fp16): a fifth of the
-// instructions of erff, for epilogues that would otherwise stall a weight-streaming kernel.
+// instructions of erff; the GELU epilogue of the first MoE matmul is a quarter of its workgroups' run time otherwise.
 __device__ __forceinline__ float gelu_erf_fast(float x) {
   const float z = fabsf(x) * 0.70710678118654752f;
   const float t = __frcp_rn(1.0f + 0.3275911f * z);
@@ -421,7 +420,7 @@ k_gather_m(const GemmArgs g) {
       for (int j = 0; j < 2; ++j) {
         const int col = n0 + wn * 64 + j * 32 + (lane & 31);
         float v = acc[i][j][e];
-        if constexpr (EPI == EPI_GELU) v = gelu_erf(v);
+        if constexpr (EPI == EPI_GELU) v = gelu_erf_fast(v);
         if constexpr (EPI == EPI_STORE) v *= scale;
         if constexpr (EPI == EPI_ATOMIC) {
           atomicAdd(reinterpret_cast<float*>(g.C) + crow * g.ldc + col, v);
@@ -678,188 +677,6 @@ k_gather_k_direct(const GemmArgs g) {
   if (wv == 3) red_recv_store<BF, CT, 3>(acc, red + RED_BUF_BYTES, g, m_base, n0, lane);
 }
 
-// ------------------------------------------------------------------------------------------------
-// GATHER_M for skinny, weight-streaming products (per-segment B: the experts of an MoE layer).
-//
-// There the time goes into reading each segment's B from HBM, ideally once.  A workgroup takes a
-// row tile of 64 gathered rows and four neighbouring column tiles, ONE PER WAVE: a wave computes
-// its 64 x 128 tile over the whole of k on its own (128 accumulation registers; no LDS, no
-// barrier, no reduction) with DB slabs of 32 k (8 KiB of B each) in flight, and the four waves
-// together read 1 KiB runs of each B row.  B rows go global -> registers with in-lane transposes
-// as in k_gather_k_direct.  The A operand needs no staging at all: an MFMA A register is 8
-// consecutive k of one row, which for K-minor A is one 16-byte load from the gathered row (lane
-// l: row l % 16 of a 16-row block, k-block l / 16).  Those loads are not coalesced across lanes,
-// which is affordable because A is small and cache-resident here.  Requires K % 32 == 0.
-// Row tiles are dealt to the XCDs in groups of 4 consecutive ones, so that the row tiles of one
-// segment read its B through the same L2 at about the same time.
-// ------------------------------------------------------------------------------------------------
-// As mfma16_acc, for code whose operands the register allocator may keep in accumulation registers
-// and copy to vector registers just before use: the leading s_nop keeps the MFMA away from such a
-// copy (an MFMA must not read a register in the issue slot after a vector instruction wrote it).
-template <bool BF>
-__device__ __forceinline__ void mfma16_acc_guarded(const uint4& a, const uint4& b, f32x4_t& c) {
-  const u32x4_t av = __builtin_bit_cast(u32x4_t, a), bv = __builtin_bit_cast(u32x4_t, b);
-  if constexpr (BF) asm("s_nop 3\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(av), "v"(bv));
-  else              asm("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(av), "v"(bv));
-}
-
-template <bool BF, int EPI, int CT, int NB, int DB>
-__global__ void __launch_bounds__(256)
-k_rows_direct(const GemmArgs g) {
-  constexpr int SK = 32, RM = 16 * NB;   // NB blocks of 16 rows per tile
-  constexpr int GR = 4;                  // consecutive row tiles that go to the same XCD
-  const int lane = threadIdx.x & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-
-  // Consecutive workgroup ids go to different XCDs (8, each with its own L2).  XCD x works on row
-  // tiles 4x .. 4x+3, 32 + 4x .. 32 + 4x+3, .. and runs a row tile's column groups back to back.
-  // (Groups stay interleaved over the XCDs because the grid is sized for the worst case and the
-  // surplus row tiles sit at its end.)
-  int tile_row, tile_grp;
-  {
-    const int tn = gridDim.x, tm = gridDim.y;
-    const int lin = blockIdx.x + tn * blockIdx.y;
-    const int full = (tm / (8 * GR)) * (8 * GR);
-    if (lin < full * tn) {
-      const int x = lin & 7, i = lin >> 3;
-      const int j = i / tn;                       // row tile number inside this XCD's sequence
-      tile_row = ((j / GR) * 8 + x) * GR + j % GR;
-      tile_grp = i - j * tn;
-    } else {
-      tile_row = lin / tn;
-      tile_grp = lin - tile_row * tn;
-    }
-  }
-  const int n0 = (tile_grp * 4 + wv) * TN;   // this wave's column tile
-  if (n0 >= g.N) return;                     // (the waves of a workgroup never synchronise)
-
-  // linear row-tile number -> (segment, tile inside segment)
-  int seg = -1, tile_in_seg = 0;
-  {
-    int before = 0;
-    for (int s0 = 0; s0 < g.nseg; s0 += 64) {
-      const int s = s0 + lane;
-      int cnt = 0;
-      if (s < g.nseg) cnt = g.seg_ptr[s + 1] - g.seg_ptr[s];
-      const int nt = (cnt + RM - 1) / RM;
-      int inc = nt;
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const int t = __shfl_up(inc, d);
-        if (lane >= d) inc += t;
-      }
-      const int total = __shfl(inc, 63);
-      if (tile_row < before + total) {
-        const unsigned long long hit = __ballot(before + inc > tile_row);
-        const int l = __builtin_ctzll(hit);
-        seg = s0 + l;
-        tile_in_seg = tile_row - (before + __shfl(inc, l) - __shfl(nt, l));
-        break;
-      }
-      before += total;
-    }
-  }
-  if (seg < 0) return;
-  seg = __builtin_amdgcn_readfirstlane(seg);
-  tile_in_seg = __builtin_amdgcn_readfirstlane(tile_in_seg);
-  const int sb = g.seg_ptr[seg];
-  const int list_begin = sb + tile_in_seg * RM;
-  const int list_len = min(RM, g.seg_ptr[seg + 1] - sb - tile_in_seg * RM);
-
-  f32x4_t acc[NB][8];
-#pragma unroll
-  for (int i = 0; i < NB; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-  const int q = lane & 15, kb = lane >> 4;
-  const char* a_src = uniform_ptr(g.A);
-  const char* b_src = uniform_ptr(reinterpret_cast<const char*>(g.B) + (int64_t)seg * g.b_seg_stride * 2);
-  const uint32_t pitch_a = (uint32_t)(g.lda * 2), pitch_b = (uint32_t)(g.ldb * 2);
-  const uint32_t b_col = (uint32_t)(n0 + 8 * q) * 2u;
-  // A: row 16 i + q of the tile (rows past the end of the list re-read its last row; their results
-  // are never stored), bytes 16 kb .. 16 kb + 15 of each 64-byte slab
-  uint32_t a_off[NB];
-#pragma unroll
-  for (int i = 0; i < NB; ++i) {
-    const int pos = list_begin + min(16 * i + q, list_len - 1);
-    const uint32_t row = g.a_gather ? (uint32_t)g.idx[pos] : (uint32_t)pos;
-    a_off[i] = __umul24(row, pitch_a) + (uint32_t)(kb * 16);
-  }
-
-  const int nslab = g.slab / SK;
-  uint4 RA[DB][NB], RB[DB][8];
-  // loads of slab s (slabs past the end re-read the last one; never used)
-  auto issue = [&](int s, uint4 (&ra)[NB], uint4 (&rb)[8]) {
-    const int sc = min(s, nslab - 1);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) rb[i] = load16(b_src, __umul24((uint32_t)(sc * SK + 8 * kb + i), pitch_b) + b_col);
-#pragma unroll
-    for (int i = 0; i < NB; ++i) ra[i] = load16(a_src, a_off[i] + (uint32_t)(sc * SK * 2));
-  };
-  // 8 NB MFMAs on one slab: the A registers are used as loaded, the B operands are transposed first
-  auto process = [&](const uint4 (&ra)[NB], const uint4 (&rb)[8]) {
-    uint4 bfr[8];
-#pragma unroll
-    for (int jb = 0; jb < 8; ++jb) bfr[jb] = transpose8x8_row(rb, jb);
-    PIT_SCHED_FENCE();
-#pragma unroll
-    for (int i = 0; i < NB; ++i)
-#pragma unroll
-      for (int jb = 0; jb < 8; ++jb) mfma16_acc_guarded<BF>(ra[i], bfr[jb], acc[i][jb]);
-    PIT_SCHED_FENCE();
-  };
-
-#pragma unroll
-  for (int u = 0; u < DB; ++u) { issue(u, RA[u], RB[u]); PIT_SCHED_FENCE(); }
-  for (int s0 = 0; s0 < nslab; s0 += DB) {
-#pragma unroll
-    for (int u = 0; u < DB; ++u) {
-      if (s0 + u < nslab) process(RA[u], RB[u]);
-      PIT_SCHED_FENCE();
-      issue(s0 + u + DB, RA[u], RB[u]);
-      PIT_SCHED_FENCE();
-    }
-  }
-  PIT_MFMA_DRAIN();
-
-  // SWrite: accumulator element e of block i is tile row 16 i + 4 kb + e; a lane holds 8 consecutive
-  // columns of it (one per jb)
-#pragma unroll
-  for (int i = 0; i < NB; ++i) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int r = 16 * i + 4 * kb + e;
-      if (r >= list_len) continue;
-      const int64_t crow = g.c_scatter ? g.idx[list_begin + r] : list_begin + r;
-      float v[8];
-#pragma unroll
-      for (int jb = 0; jb < 8; ++jb) v[jb] = acc[i][jb][e];
-      if constexpr (EPI == EPI_GELU) {
-#pragma unroll
-        for (int jb = 0; jb < 8; ++jb) v[jb] = gelu_erf_fast(v[jb]);
-      } else {
-        if (g.gate) {
-          const float sc = g.gate[crow];
-#pragma unroll
-          for (int jb = 0; jb < 8; ++jb) v[jb] *= sc;
-        }
-      }
-      const int col = n0 + 8 * q;
-      if constexpr (CT == 0) {
-        float* d = reinterpret_cast<float*>(g.C) + crow * g.ldc + col;
-        *reinterpret_cast<float4*>(d) = make_float4(v[0], v[1], v[2], v[3]);
-        *reinterpret_cast<float4*>(d + 4) = make_float4(v[4], v[5], v[6], v[7]);
-      } else {
-        uint32_t w[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) w[x] = (uint32_t)f32_to_in<BF>(v[2 * x]) | ((uint32_t)f32_to_in<BF>(v[2 * x + 1]) << 16);
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(g.C) + crow * g.ldc + col) = make_uint4(w[0], w[1], w[2], w[3]);
-      }
-    }
-  }
-}
-
 // Zero rows of C that no index entry names (single-segment GATHER_M): the list is ascending, so a
 // row is uncovered iff a binary search misses it.  One wave per row, 16-byte stores.
 template <int ESIZE>
@@ -900,17 +717,6 @@ static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
     PIT_LAUNCH_CHECK();
     return PIT_OK;
   } else {
-    if constexpr (EPI != EPI_ATOMIC) {
-      // per-segment B (expert weights): the weight-streaming kernel, on 64-row tiles
-      if (g.b_seg_stride != 0 && !g.slab_per_seg && g.slab % 32 == 0 && g.slab > 0) {
-        constexpr int NB = 4, RM = 16 * NB, DB = 5;
-        // sum over segments of ceil(count / RM) <= M / RM + nseg row tiles; 4 column tiles per workgroup
-        const dim3 grid64((grid.x + 3) / 4, (unsigned)(g.M / RM + g.nseg));
-        hipLaunchKernelGGL((k_rows_direct<BF, EPI, CT, NB, DB>), grid64, dim3(256), 0, st, g);
-        PIT_LAUNCH_CHECK();
-        return PIT_OK;
-      }
-    }
     hipLaunchKernelGGL((k_gather_m<BF, EPI, CT>), grid, dim3(256), 0, st, g);
     PIT_LAUNCH_CHECK();
     return PIT_OK;
