@@ -159,7 +159,8 @@ size_t pit_moe_workspace(int T, int d_model, int d_ff, int E);
  * Y[t, :] = gate[t] * ( act( X[t, :] . W1[e] ) . W2[e] ),   e = d_expert_id[t]   (top-1).
  *   d_X   [T x d_model] in_dt, row-major, contiguous.     d_Y  [T x d_model] y_dt (PIT_F32/BF16/F16).
  *   d_W1  [E][d_model][d_ff] in_dt, contiguous.            d_W2 [E][d_ff][d_model] in_dt, contiguous.
- *   d_gate [T] fp32 or NULL (= 1).    act: 0 = exact (erf) GELU, 1 = identity.
+ *   d_gate [T] fp32 or NULL (= 1).    act: 0 = erf-form GELU x (1 + erf(x / sqrt 2)) / 2 (erf evaluated
+ *   to 1.5e-7 absolute error, below the rounding of the hidden row to the input type), 1 = identity.
  *   The hidden activations are kept in in_dt (rounded nearest-even) between the two matmuls.
  *   d_status (may be NULL): set to the number of tokens whose expert id is outside [0, E); those
  *   tokens' rows of Y are zero.
