@@ -160,6 +160,33 @@ def sparsity_after_cover(src: np.ndarray, mt_rows: int, mt_cols: int) -> float:
     return 1.0 - cover_count(src, mt_rows, mt_cols) * mt_rows * mt_cols / float(rows * cols)
 
 
+def select_kernel(samples, candidates):
+    """Kernel selection (Algorithm 1, Section 3.2 "Micro-tile and Kernel Selection").
+
+    ``candidates`` is the algorithm's double loop over dense computation tiles T and PIT-axes A
+    written out: each entry is a dict with the micro-tile shape that (T, A) induces on the sparse
+    operand (``mt_rows``, ``mt_cols``) and ``tile_cost``, the profiled running time of the sparse
+    kernel per covered micro-tile.  An entry with ``dense=True`` stands for the dense kernel: it
+    processes every micro-tile of the grid whatever the data, which is how low sparsity falls back
+    to dense computation.  For every candidate the cost is the sum over the sparsity samples of
+    CoverAlgo(sample, micro-tile) * tile_cost; the result is (index of the cheapest candidate, the
+    first one among equals; list of all costs).  parity pinned in tests/test_oracle_select.py."""
+    best, best_cost, costs = -1, math.inf, []
+    for i, c in enumerate(candidates):
+        cost = 0.0
+        for D in samples:
+            rows, cols = D.shape
+            if c.get("dense", False):
+                num_tiles = (rows // c["mt_rows"]) * (cols // c["mt_cols"])
+            else:
+                num_tiles = cover_count(D, c["mt_rows"], c["mt_cols"])
+            cost += num_tiles * c["tile_cost"]
+        costs.append(cost)
+        if cost < best_cost:
+            best, best_cost = i, cost
+    return best, costs
+
+
 # ------------------------------------------------------------------------------------------------
 # GEMM (Table 1 "MatMul": C[m,n] += A[m,k] * B[k,n])
 # ------------------------------------------------------------------------------------------------

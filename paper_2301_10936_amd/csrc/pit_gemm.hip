@@ -603,7 +603,7 @@ k_gather_k_direct(const GemmArgs g) {
       for (int i = 0; i < 8; ++i) kk[i] = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * kb + i) * 4, kraw);
     }
     PIT_SCHED_FENCE();
-    asm volatile("s_nop 3");
+    asm volatile("s_nop 7");
     PIT_SCHED_FENCE();
 #pragma unroll
     for (int ja = 0; ja < 8; ++ja) {
