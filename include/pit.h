@@ -108,6 +108,50 @@ int pit_build_route_index(const int32_t* d_expert_id, int T, int E, const pit_in
                           int32_t* d_status, void* d_ws, size_t ws_bytes, pit_stream stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * 1b. Micro-tile and kernel selection (paper Section 3.2, Algorithm 1)
+ * ------------------------------------------------------------------------------------------- */
+
+/* Bytes of device workspace pit_cover_count needs for this problem (0 on invalid arguments). */
+size_t pit_cover_count_workspace(int rows, int cols, int mt_rows, int mt_cols);
+
+/*
+ * CoverAlgo of Algorithm 1: the number of mt_rows x mt_cols micro-tiles needed to cover every
+ * non-zero of the [rows x cols] tensor `d_src` (same zero test and arguments as pit_build_index;
+ * the count does not depend on which axis is the PIT-axis).  *d_count (device, int32) receives
+ * the count when the enqueued work completes; the caller reads it back when it wants to decide.
+ * Errors as pit_build_index.  rows*cols == 0 gives 0.
+ */
+int pit_cover_count(const void* d_src, int dt, int rows, int cols, int64_t ld, int mt_rows, int mt_cols,
+                    int32_t* d_count, void* d_ws, size_t ws_bytes, pit_stream stream);
+
+/*
+ * One (dense computation tile, PIT-axis) pair of Algorithm 1's double loop: the micro-tile shape
+ * the pair induces on the sparse operand, the profiled running time of its sparse kernel per
+ * covered micro-tile (any unit, the same for all candidates), and whether it is the dense
+ * kernel, which processes every micro-tile of the grid whatever the data (the fallback for low
+ * sparsity).
+ */
+typedef struct pit_kernel_candidate {
+  int32_t mt_rows, mt_cols;
+  int32_t dense;       /* 0 = sparse kernel, 1 = dense kernel */
+  double  tile_cost;
+} pit_kernel_candidate;
+
+/*
+ * Kernel selection (Algorithm 1).  HOST-only: no device work, no stream.
+ *   cand       [ncand] candidates (host)
+ *   num_tiles  [nsamples x ncand] (host, row-major): CoverAlgo of sample i for candidate j, e.g.
+ *              read back from pit_cover_count; ignored for dense candidates
+ *   grid_tiles [nsamples x ncand] (host): number of micro-tiles of candidate j in sample i's whole
+ *              grid (rows/mt_rows * cols/mt_cols); used for dense candidates
+ *   cost_out   [ncand] (host) or NULL: receives sum over samples of tiles * tile_cost
+ *   best_out   receives the index of the cheapest candidate, the first one among equals
+ * Errors: PIT_EINVAL (NULL pointers, ncand <= 0, nsamples < 0, negative counts or costs).
+ */
+int pit_select_kernel(const pit_kernel_candidate* cand, int ncand, const int64_t* num_tiles,
+                      const int64_t* grid_tiles, int nsamples, double* cost_out, int* best_out);
+
+/* ---------------------------------------------------------------------------------------------
  * 2-4. SRead -> dense MFMA tile -> SWrite  (paper Section 3.1; Section 2.3 for the two cases)
  * ------------------------------------------------------------------------------------------- */
 

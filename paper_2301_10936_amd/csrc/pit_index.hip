@@ -10,6 +10,7 @@
 //           written to its slot (lane b of a wave owns bit b, so stores are coalesced).
 // The tensor itself is never re-formatted.
 #include "pit_common.hpp"
+#include <algorithm>
 
 namespace pit {
 namespace {
@@ -334,6 +335,17 @@ k_emit_chunked(const u64* __restrict__ words, const int32_t* __restrict__ seg_cn
   }
 }
 
+// total number of set bits of the bitmap (CoverAlgo): one atomic per workgroup into a zeroed counter
+__global__ void __launch_bounds__(256)
+k_count_bits(const u64* __restrict__ words, int64_t nwords, int32_t* __restrict__ count) {
+  __shared__ int red[4];
+  int part = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nwords; i += (int64_t)gridDim.x * 256)
+    part += __popcll(words[i]);
+  const int total = block_sum_256(part, red);
+  if (threadIdx.x == 0 && total != 0) atomicAdd(count, total);
+}
+
 __global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -397,6 +409,36 @@ int launch_emit(const Layout& L, const u64* words, int32_t* cnt, const uint32_t*
 
 using namespace pit;
 
+// pass 1: the bitmap of non-empty micro-tiles (and, if occ != nullptr, their element occupancy)
+static int launch_bitmap(const Layout& L, const void* d_src, int esize, int rows, int cols, int64_t ld,
+                         int mt_rows, int mt_cols, int pit_dim, bool want_bits, u64* words, uint32_t* occ,
+                         hipStream_t st) {
+  const int64_t mt_bytes = (int64_t)mt_cols * esize;
+  const int64_t row_bytes = (int64_t)cols * esize;
+  const bool vec_ok = aligned(d_src, 16) && (ld * esize) % 16 == 0 && row_bytes % 16 == 0 && row_bytes < (1ll << 31);
+  if (pit_dim == 0 && mt_rows == 1 && !want_bits && vec_ok && mt_bytes >= 16 && mt_bytes <= 1024 &&
+      (mt_bytes & (mt_bytes - 1)) == 0) {
+    const int lpm = (int)(mt_bytes / 16);
+    dim3 grid((unsigned)ceil_div(row_bytes, 1024), (unsigned)ceil_div(rows, 64));
+    if (esize == 1)      hipLaunchKernelGGL(k_bitmap_rows<1>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
+    else if (esize == 2) hipLaunchKernelGGL(k_bitmap_rows<2>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
+    else                 hipLaunchKernelGGL(k_bitmap_rows<4>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
+  } else if (pit_dim == 1 && mt_cols == 1 && esize == 1 && vec_ok && cols % 16 == 0) {
+    const int chunks = (L.W * 64 + 1023) / 1024;
+    const int64_t waves = (int64_t)L.nseg * chunks;
+    hipLaunchKernelGGL(k_bitmap_cols_u8, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st,
+                       reinterpret_cast<const uint8_t*>(d_src), ld, mt_rows, cols, L.nseg, L.npit, L.W, words, occ);
+  } else {
+    const int64_t waves = (int64_t)L.nseg * L.W;
+    dim3 grid((unsigned)ceil_div(waves, 4));
+    if (esize == 1)      hipLaunchKernelGGL(k_bitmap_generic<1>, grid, dim3(256), 0, st, d_src, ld, mt_rows, mt_cols, pit_dim, L.nseg, L.npit, L.W, words, occ);
+    else if (esize == 2) hipLaunchKernelGGL(k_bitmap_generic<2>, grid, dim3(256), 0, st, d_src, ld, mt_rows, mt_cols, pit_dim, L.nseg, L.npit, L.W, words, occ);
+    else                 hipLaunchKernelGGL(k_bitmap_generic<4>, grid, dim3(256), 0, st, d_src, ld, mt_rows, mt_cols, pit_dim, L.nseg, L.npit, L.W, words, occ);
+  }
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
+}
+
 extern "C" size_t pit_build_index_workspace(int rows, int cols, int mt_rows, int mt_cols, int pit_dim, int want_bits) {
   if (rows < 0 || cols < 0 || mt_rows <= 0 || mt_cols <= 0 || (pit_dim != 0 && pit_dim != 1)) return 0;
   if (rows % mt_rows || cols % mt_cols) return 0;
@@ -427,30 +469,64 @@ extern "C" int pit_build_index(const void* d_src, int dt, int rows, int cols, in
   uint32_t* occ = want_bits ? reinterpret_cast<uint32_t*>(ws + L.words_bytes) : nullptr;
   int32_t* cnt = reinterpret_cast<int32_t*>(ws + L.words_bytes + L.occ_bytes);
 
-  const int64_t mt_bytes = (int64_t)mt_cols * esize;
-  const int64_t row_bytes = (int64_t)cols * esize;
-  const bool vec_ok = aligned(d_src, 16) && (ld * esize) % 16 == 0 && row_bytes % 16 == 0 && row_bytes < (1ll << 31);
-  if (pit_dim == 0 && mt_rows == 1 && !want_bits && vec_ok && mt_bytes >= 16 && mt_bytes <= 1024 &&
-      (mt_bytes & (mt_bytes - 1)) == 0) {
-    const int lpm = (int)(mt_bytes / 16);
-    dim3 grid((unsigned)ceil_div(row_bytes, 1024), (unsigned)ceil_div(rows, 64));
-    if (esize == 1)      hipLaunchKernelGGL(k_bitmap_rows<1>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
-    else if (esize == 2) hipLaunchKernelGGL(k_bitmap_rows<2>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
-    else                 hipLaunchKernelGGL(k_bitmap_rows<4>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
-  } else if (pit_dim == 1 && mt_cols == 1 && esize == 1 && vec_ok && cols % 16 == 0) {
-    const int chunks = (L.W * 64 + 1023) / 1024;
-    const int64_t waves = (int64_t)L.nseg * chunks;
-    hipLaunchKernelGGL(k_bitmap_cols_u8, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st,
-                       reinterpret_cast<const uint8_t*>(d_src), ld, mt_rows, cols, L.nseg, L.npit, L.W, words, occ);
-  } else {
-    const int64_t waves = (int64_t)L.nseg * L.W;
-    dim3 grid((unsigned)ceil_div(waves, 4));
-    if (esize == 1)      hipLaunchKernelGGL(k_bitmap_generic<1>, grid, dim3(256), 0, st, d_src, ld, mt_rows, mt_cols, pit_dim, L.nseg, L.npit, L.W, words, occ);
-    else if (esize == 2) hipLaunchKernelGGL(k_bitmap_generic<2>, grid, dim3(256), 0, st, d_src, ld, mt_rows, mt_cols, pit_dim, L.nseg, L.npit, L.W, words, occ);
-    else                 hipLaunchKernelGGL(k_bitmap_generic<4>, grid, dim3(256), 0, st, d_src, ld, mt_rows, mt_cols, pit_dim, L.nseg, L.npit, L.W, words, occ);
-  }
-  PIT_LAUNCH_CHECK();
+  const int rc = launch_bitmap(L, d_src, esize, rows, cols, ld, mt_rows, mt_cols, pit_dim, want_bits, words, occ, st);
+  if (rc != PIT_OK) return rc;
   return launch_emit(L, words, cnt, occ, out, 0, nullptr, st);
+}
+
+// The count does not depend on the PIT-axis; byte masks with column-shaped micro-tiles take the
+// layout whose bitmap pass reads rows of the mask with 16-byte loads.
+static int cover_count_axis(int esize, int mt_rows, int mt_cols) { return (esize == 1 && mt_cols == 1 && mt_rows > 1) ? 1 : 0; }
+
+extern "C" size_t pit_cover_count_workspace(int rows, int cols, int mt_rows, int mt_cols) {
+  return std::max(pit_build_index_workspace(rows, cols, mt_rows, mt_cols, 0, 0),
+                  pit_build_index_workspace(rows, cols, mt_rows, mt_cols, 1, 0));
+}
+
+extern "C" int pit_cover_count(const void* d_src, int dt, int rows, int cols, int64_t ld, int mt_rows, int mt_cols,
+                               int32_t* d_count, void* d_ws, size_t ws_bytes, pit_stream stream) {
+  const int esize = dtype_size(dt);
+  if (!d_count || esize == 0) return PIT_EINVAL;
+  if (rows < 0 || cols < 0 || mt_rows <= 0 || mt_cols <= 0) return PIT_ESHAPE;
+  if (rows % mt_rows || cols % mt_cols) return PIT_ESHAPE;
+  if (ld < cols) return PIT_EINVAL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, d_count, 1, 0);
+  PIT_LAUNCH_CHECK();
+  const int pit_dim = cover_count_axis(esize, mt_rows, mt_cols);
+  const Layout L = make_layout(rows, cols, mt_rows, mt_cols, pit_dim, 0);
+  if (L.nseg == 0 || L.npit == 0) return PIT_OK;
+  if (!d_src || !d_ws || !aligned(d_ws, 8) || !aligned(d_src, esize)) return PIT_EINVAL;
+  if (ws_bytes < pit_cover_count_workspace(rows, cols, mt_rows, mt_cols)) return PIT_ECAPACITY;
+  u64* words = reinterpret_cast<u64*>(d_ws);
+  const int rc = launch_bitmap(L, d_src, esize, rows, cols, ld, mt_rows, mt_cols, pit_dim, false, words, nullptr, st);
+  if (rc != PIT_OK) return rc;
+  const int64_t nwords = (int64_t)L.nseg * L.W;
+  const unsigned blocks = (unsigned)std::min<int64_t>(ceil_div(nwords, 256), 1024);
+  hipLaunchKernelGGL(k_count_bits, dim3(blocks), dim3(256), 0, st, words, nwords, d_count);
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
+}
+
+extern "C" int pit_select_kernel(const pit_kernel_candidate* cand, int ncand, const int64_t* num_tiles,
+                                 const int64_t* grid_tiles, int nsamples, double* cost_out, int* best_out) {
+  if (!cand || !best_out || ncand <= 0 || nsamples < 0) return PIT_EINVAL;
+  if (nsamples > 0 && (!num_tiles || !grid_tiles)) return PIT_EINVAL;
+  int best = -1;
+  double best_cost = 0.0;
+  for (int j = 0; j < ncand; ++j) {
+    if (!(cand[j].tile_cost >= 0.0) || cand[j].mt_rows <= 0 || cand[j].mt_cols <= 0) return PIT_EINVAL;
+    double cost = 0.0;
+    for (int i = 0; i < nsamples; ++i) {
+      const int64_t n = cand[j].dense ? grid_tiles[(int64_t)i * ncand + j] : num_tiles[(int64_t)i * ncand + j];
+      if (n < 0) return PIT_EINVAL;
+      cost += (double)n * cand[j].tile_cost;
+    }
+    if (cost_out) cost_out[j] = cost;
+    if (best < 0 || cost < best_cost) { best = j; best_cost = cost; }
+  }
+  *best_out = best;
+  return PIT_OK;
 }
 
 extern "C" size_t pit_build_route_index_workspace(int T, int E) {

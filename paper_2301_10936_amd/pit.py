@@ -24,7 +24,8 @@ PIT_GEMM_GATHER_M, PIT_GEMM_GATHER_K = 0, 1
 _STATUS = {0: "PIT_OK", -1: "PIT_EINVAL", -2: "PIT_ESHAPE", -3: "PIT_ECAPACITY", -4: "PIT_EHIP"}
 
 EXPORTS = ["pit_last_hip_error", "pit_version", "pit_build_index_workspace", "pit_build_index",
-           "pit_build_route_index_workspace", "pit_build_route_index", "pit_sread_gemm",
+           "pit_build_route_index_workspace", "pit_build_route_index",
+           "pit_cover_count_workspace", "pit_cover_count", "pit_select_kernel", "pit_sread_gemm",
            "pit_moe_workspace", "pit_moe_dispatch_gemm", "pit_sparse_attn_workspace", "pit_sparse_attn"]
 
 
@@ -45,6 +46,20 @@ _lib.pit_build_route_index_workspace.restype = c_sz
 _lib.pit_build_route_index_workspace.argtypes = [c_int, c_int]
 _lib.pit_build_route_index.restype = c_int
 _lib.pit_build_route_index.argtypes = [c_vp, c_int, c_int, _P, c_vp, c_vp, c_sz, c_vp]
+
+
+class _CCandidate(ctypes.Structure):
+    _fields_ = [("mt_rows", ctypes.c_int32), ("mt_cols", ctypes.c_int32), ("dense", ctypes.c_int32),
+                ("tile_cost", ctypes.c_double)]
+
+
+_lib.pit_cover_count_workspace.restype = c_sz
+_lib.pit_cover_count_workspace.argtypes = [c_int] * 4
+_lib.pit_cover_count.restype = c_int
+_lib.pit_cover_count.argtypes = [c_vp, c_int, c_int, c_int, c_i64, c_int, c_int, c_vp, c_vp, c_sz, c_vp]
+_lib.pit_select_kernel.restype = c_int
+_lib.pit_select_kernel.argtypes = [ctypes.POINTER(_CCandidate), c_int, ctypes.POINTER(c_i64), ctypes.POINTER(c_i64),
+                                   c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_int)]
 _lib.pit_sread_gemm.restype = c_int
 _lib.pit_sread_gemm.argtypes = [c_int, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_int, c_int, c_int, c_int, c_int,
                                 _P, c_int, c_int, c_vp]
@@ -154,6 +169,41 @@ def pit_build_route_index(expert_id: torch.Tensor, E: int, out: PitIndex | None 
     _check(_lib.pit_build_route_index(expert_id.data_ptr(), T, E, ctypes.byref(ci), _ptr(status), ws.data_ptr(),
                                       ws.numel(), _stream()), "pit_build_route_index")
     return out
+
+
+def pit_cover_count_workspace(rows, cols, mt_rows, mt_cols) -> int:
+    return _lib.pit_cover_count_workspace(rows, cols, mt_rows, mt_cols)
+
+
+def pit_cover_count(src: torch.Tensor, mt_rows: int, mt_cols: int, out: torch.Tensor | None = None,
+                    ws: torch.Tensor | None = None) -> torch.Tensor:
+    """CoverAlgo of Algorithm 1 on a 2-D tensor; returns a device int32[1].  See include/pit.h."""
+    assert src.dim() == 2 and src.stride(1) == 1
+    rows, cols = src.shape
+    if out is None:
+        out = torch.empty(1, dtype=torch.int32, device=src.device)
+    if ws is None:
+        ws = torch.empty(max(pit_cover_count_workspace(rows, cols, mt_rows, mt_cols), 8), dtype=torch.uint8,
+                         device=src.device)
+    _check(_lib.pit_cover_count(src.data_ptr(), _dt(src), rows, cols, src.stride(0) if rows > 1 else max(cols, src.stride(0)),
+                                mt_rows, mt_cols, out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()),
+           "pit_cover_count")
+    return out
+
+
+def pit_select_kernel(candidates, num_tiles, grid_tiles):
+    """Algorithm 1 on the host.  candidates: sequence of dicts (mt_rows, mt_cols, tile_cost, optional dense);
+    num_tiles / grid_tiles: [nsamples][ncand] integers.  Returns (best index, list of costs)."""
+    ncand, nsamples = len(candidates), len(num_tiles)
+    cands = (_CCandidate * max(ncand, 1))()
+    for j, c in enumerate(candidates):
+        cands[j] = _CCandidate(int(c["mt_rows"]), int(c["mt_cols"]), int(bool(c.get("dense", False))), float(c["tile_cost"]))
+    flat_n = (c_i64 * max(ncand * nsamples, 1))(*[int(v) for row in num_tiles for v in row])
+    flat_g = (c_i64 * max(ncand * nsamples, 1))(*[int(v) for row in grid_tiles for v in row])
+    costs = (ctypes.c_double * max(ncand, 1))()
+    best = c_int(-1)
+    _check(_lib.pit_select_kernel(cands, ncand, flat_n, flat_g, nsamples, costs, ctypes.byref(best)), "pit_select_kernel")
+    return best.value, [costs[j] for j in range(ncand)]
 
 
 def pit_sread_gemm(mode: int, A: torch.Tensor, B: torch.Tensor, ix: PitIndex, mt: int, M: int, N: int, K: int,

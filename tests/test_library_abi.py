@@ -47,3 +47,30 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.pit_sread_gemm(0, None, 0, None, 0, None, 0, 128, 100, 64, pit.PIT_BF16, pit.PIT_F32, ctypes.byref(ci2), 64, 1, None) == pit.PIT_ESHAPE
     assert lib.pit_moe_workspace(4096, 768, 3072, 64) > 4096 * 3072 * 2
     assert lib.pit_moe_dispatch_gemm(None, None, None, None, None, None, pit.PIT_F32, 16, 100, 128, 2, pit.PIT_BF16, 0, None, None, 0, None) == pit.PIT_ESHAPE
+
+
+def test_select_kernel_on_the_host_matches_the_oracle():
+    """pit_select_kernel is host-only: check it here against the oracle's Algorithm 1 on counts the
+    oracle's CoverAlgo produced (so the comparison covers the cost sum, the dense rule and the tie rule)."""
+    import numpy as np
+    from oracle import pit_oracle as orc
+    from paper_2301_10936_amd import pit, workloads as wl
+    cands = [{"mt_rows": 2, "mt_cols": 1, "tile_cost": 2.0},
+             {"mt_rows": 8, "mt_cols": 1, "tile_cost": 3.5},
+             {"mt_rows": 32, "mt_cols": 1, "tile_cost": 9.0},
+             {"mt_rows": 32, "mt_cols": 1, "tile_cost": 8.0, "dense": True},
+             {"mt_rows": 8, "mt_cols": 1, "tile_cost": 3.5}]          # equal to candidate 1: the first one wins
+    for s in (0.999, 0.97, 0.8, 0.3):
+        samples = [wl.iid_block_mask(256, 128, 2, 1, s, seed=k) for k in range(3)]
+        num = [[orc.cover_count(D, c["mt_rows"], c["mt_cols"]) for c in cands] for D in samples]
+        grid = [[(D.shape[0] // c["mt_rows"]) * (D.shape[1] // c["mt_cols"]) for c in cands] for D in samples]
+        best, costs = pit.pit_select_kernel(cands, num, grid)
+        want_best, want_costs = orc.select_kernel(samples, cands)
+        assert best == want_best and best != 4
+        assert np.allclose(costs, want_costs, rtol=1e-12)
+    assert pit.pit_select_kernel(cands, [], []) == (0, [0.0] * 5)
+    import pytest
+    with pytest.raises(pit.PitError):
+        pit.pit_select_kernel([{"mt_rows": 0, "mt_cols": 1, "tile_cost": 1.0}], [[1]], [[1]])
+    with pytest.raises(pit.PitError):
+        pit.pit_select_kernel(cands, [[-1] * 5], [[1] * 5])
