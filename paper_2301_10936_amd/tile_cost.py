@@ -1,0 +1,95 @@
+"""Offline profiling for kernel selection (paper Section 3.2: the tile cost is profiled once per
+operator and GPU type, independent of model, shape and sparsity pattern).
+
+Measures, on the GPU this runs on, the running time per covered micro-tile of every (dense tile,
+PIT-axis) pair the library offers for C[M, N] = A[M, K] . B[K, N] with a sparse A, and prints the
+table as JSON -- the ``tile_cost`` values of pit_select_kernel's candidates.
+
+    python -m paper_2301_10936_amd.tile_cost [--n 2048] [--out tile_cost.json]
+
+Candidates (micro-tile shape on A as stored [M, K]):
+    gather_k     128 x 1   k is the PIT-axis (A supplied K-major), pit_sread_gemm(GATHER_K, mt=128)
+    gather_m_S   1 x S     m is the PIT-axis, k-slabs of S in {32, 64, 128}, pit_sread_gemm(GATHER_M, mt=S)
+    gather_m_row 1 x K     m is the PIT-axis, whole rows, pit_sread_gemm(GATHER_M, mt=K)
+The dense kernel is the same tile with every micro-tile listed; its cost per micro-tile is the
+cost measured at full cover.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+from . import pit, workloads as wl
+
+
+def _dev(bits):
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def _time(fn, reps=20):
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e-3
+
+
+def measure(M=2048, K=4096, N=2048, keep=0.5, seed=0):
+    g = np.random.default_rng(seed)
+    B = _dev(wl.to_bf16_bits(g.standard_normal((K, N)).astype(np.float32)))
+    table = {}
+
+    def gather_k(frac):
+        live = g.random((K, M // 128)) < frac
+        At = np.repeat(live, 128, axis=1).astype(np.float32) * g.standard_normal((K, M)).astype(np.float32)
+        tA = _dev(wl.to_bf16_bits(At))
+        ix = pit.pit_build_index(tA, 1, 128, 0)
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        t = _time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, B, ix, 128, M, N, K, out=C))
+        return t / max(int(live.sum()), 1)
+
+    def gather_m(slab, frac):
+        live = g.random((M, K // slab)) < frac
+        A = np.repeat(live, slab, axis=1).astype(np.float32) * g.standard_normal((M, K)).astype(np.float32)
+        tA = _dev(wl.to_bf16_bits(A))
+        ix = pit.pit_build_index(tA, 1, slab, 0)
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        t = _time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, tA, B, ix, slab, M, N, K, out=C))
+        return t / max(int(live.sum()), 1)
+
+    for name, fn in [("gather_k", gather_k)] + [(f"gather_m_{s}", (lambda fr, s=s: gather_m(s, fr))) for s in (32, 64, 128, K)]:
+        key = name if not name.endswith(str(K)) else "gather_m_row"
+        table[key] = {"sparse_ns_per_tile": fn(keep) * 1e9, "dense_ns_per_tile": fn(1.0) * 1e9}
+    shapes = {"gather_k": [128, 1], "gather_m_32": [1, 32], "gather_m_64": [1, 64], "gather_m_128": [1, 128],
+              "gather_m_row": [1, K]}
+    return {"device": torch.cuda.get_device_name(0), "M": M, "K": K, "N": N, "keep": keep,
+            "candidates": {k: {"micro_tile": shapes[k], **v} for k, v in table.items()}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--n", type=int, default=2048)
+    ap.add_argument("--out", default=None)
+    a = ap.parse_args()
+    if not torch.cuda.is_available():
+        print("tile_cost: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    t0 = time.time()
+    res = measure(N=a.n)
+    res["seconds"] = round(time.time() - t0, 1)
+    txt = json.dumps(res, indent=1)
+    print(txt)
+    if a.out:
+        open(a.out, "w").write(txt + "\n")
+
+
+if __name__ == "__main__":
+    main()

@@ -74,3 +74,26 @@ def test_select_kernel_on_the_host_matches_the_oracle():
         pit.pit_select_kernel([{"mt_rows": 0, "mt_cols": 1, "tile_cost": 1.0}], [[1]], [[1]])
     with pytest.raises(pit.PitError):
         pit.pit_select_kernel(cands, [[-1] * 5], [[1] * 5])
+
+
+def test_selection_with_the_profiled_tile_costs():
+    """The committed offline profile (paper_2301_10936_amd/tile_cost.py, one MI355X) drives Algorithm 1 as
+    the paper describes: with iid ReLU zeros nearly every 128 x 1 micro-tile is live and the dense kernel wins;
+    with zeros correlated across tokens the sparse kernel wins."""
+    import json
+    import os
+    import numpy as np
+    from oracle import pit_oracle as orc
+    from paper_2301_10936_amd import pit, workloads as wl
+    here = os.path.dirname(os.path.abspath(pit.__file__))
+    prof = json.load(open(os.path.join(here, "tile_cost_mi355x.json")))["candidates"]["gather_k"]
+    cands = [{"mt_rows": 1, "mt_cols": 128, "tile_cost": prof["sparse_ns_per_tile"]},
+             {"mt_rows": 1, "mt_cols": 128, "tile_cost": prof["dense_ns_per_tile"], "dense": True}]
+    picks = {}
+    for name, prob in (("iid", None), ("correlated", 0.25)):
+        w = wl.relu_ffn(M=512, K=1024, N=128, seed=1, channel_live_prob=prob)     # Xt is [K, M]: micro-tile 1 x 128
+        num = [[orc.cover_count(w.Xt, 1, 128)] * 2]
+        grid = [[w.Xt.shape[0] * (w.Xt.shape[1] // 128)] * 2]
+        picks[name] = pit.pit_select_kernel(cands, num, grid)[0]
+        assert picks[name] == orc.select_kernel([orc.to_f64(w.Xt)], cands)[0]
+    assert picks == {"iid": 1, "correlated": 0}
