@@ -159,6 +159,163 @@ k_bitmap_cols_u8(const uint8_t* __restrict__ src, int64_t ld, int mt_rows, int c
 }
 
 // ----------------------------------------------------------------------------------------------
+// pass 1, fast path C: any micro-tile of mt_rows x mt_bytes with mt_bytes a power of two up to
+// 1 KiB, either PIT-axis, no occupancy bits.  A workgroup streams 64 rows x 1 KiB exactly like
+// path A (16 coalesced row loads of 16 B per lane in flight per wave); what differs is how the
+// per-lane results become bitmap bits.
+//   F       flags per lane: 16 / mt_bytes for micro-tiles narrower than one load, else 1 (then
+//           lpm = mt_bytes / 16 lanes share a micro-tile and a ballot joins them)
+//   rows    the rows of one micro-tile are OR-ed in registers and flushed at its last row; the
+//           flush ORs the tile flags into an LDS bit matrix of the workgroup's micro-tiles, laid
+//           out the way the bitmap wants them: PIT_DIM 1 -> [tile row][tile column bits],
+//           PIT_DIM 0 -> [tile column][tile row bits]
+//   output  direct != 0: the workgroup owns whole 32/64-bit units of the bitmap and stores them;
+//           direct == 0: micro-tiles or bitmap units are shared between workgroups, which then
+//           OR their parts into a bitmap the host has cleared (OR commutes: the result does not
+//           depend on the order of arrival).
+// ----------------------------------------------------------------------------------------------
+template <int ESIZE, int F>
+__device__ __forceinline__ uint32_t tile_flags(const uint4& v) {
+  constexpr uint32_t M = ESIZE == 1 ? 0xFFFFFFFFu : (ESIZE == 2 ? 0x7FFF7FFFu : 0x7FFFFFFFu);
+  const uint32_t d[4] = {v.x & M, v.y & M, v.z & M, v.w & M};
+  uint32_t r = 0;
+  if (F == 1) {
+    r = (d[0] | d[1] | d[2] | d[3]) != 0 ? 1u : 0u;
+  } else if (F == 2) {
+    r = ((d[0] | d[1]) != 0 ? 1u : 0u) | ((d[2] | d[3]) != 0 ? 2u : 0u);
+  } else if (F == 4) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r |= (d[k] != 0 ? 1u : 0u) << k;
+  } else if (F == 8) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      r |= ((d[k] & 0xFFFFu) != 0 ? 1u : 0u) << (2 * k);
+      r |= ((d[k] >> 16) != 0 ? 1u : 0u) << (2 * k + 1);
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      // bit 7 of every non-zero byte, then the four of them gathered into bits 24..27
+      const uint32_t t = (((d[k] & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | d[k]) & 0x80808080u;
+      r |= ((((t >> 7) * 0x01020408u) >> 24) & 0xFu) << (4 * k);
+    }
+  }
+  return r;
+}
+
+template <int ESIZE, int F, int PIT_DIM>
+__global__ void __launch_bounds__(256)
+k_bitmap_tiles(const void* __restrict__ src, int64_t ld_bytes, int rows, int row_bytes, int mt_rows, int lpm,
+               int nseg, int W, int direct, uint32_t* __restrict__ words32) {
+  __shared__ uint32_t T[2048];   // PIT_DIM 1: [64 tile rows][32 x 32 column bits]; PIT_DIM 0: [1024 tile columns][2 x 32 row bits]
+  const int tid = threadIdx.x, wv = tid >> 6, ln = lane_id();
+  const int strip = blockIdx.x;
+  const int rblk = blockIdx.y * 64;
+  const int rbase = rblk + wv * 16;
+  const int64_t byte0 = (int64_t)strip * 1024 + ln * 16;
+  const char* base = reinterpret_cast<const char*>(src) + byte0;
+  const bool col_ok = byte0 < row_bytes;
+  uint4 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    v[i] = make_uint4(0, 0, 0, 0);
+    if (col_ok && rbase + i < rows) v[i] = *reinterpret_cast<const uint4*>(base + (int64_t)(rbase + i) * ld_bytes);
+  }
+  for (int i = tid; i < 2048; i += 256) T[i] = 0;
+  __syncthreads();
+
+  const int nb = F == 1 ? 64 / lpm : 64 * F;            // micro-tile columns per strip
+  const u64 lmask = lpm >= 64 ? ~0ull : ((1ull << lpm) - 1ull);
+  const int sh = (ln < nb ? ln : 0) * lpm;
+  const int tr_first = rblk / mt_rows;
+  int trl = rbase / mt_rows - tr_first;
+  int rem = rbase % mt_rows;
+  uint4 cur = make_uint4(0, 0, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (rbase + i < rows) {
+      cur.x |= v[i].x; cur.y |= v[i].y; cur.z |= v[i].z; cur.w |= v[i].w;
+      ++rem;
+      if (rem == mt_rows || i == 15) {
+        const uint32_t fl = tile_flags<ESIZE, F>(cur);
+        if (F == 1) {
+          const u64 b = __ballot(fl != 0);
+          if (b != 0) {
+            const bool bit = ln < nb && ((b >> sh) & lmask) != 0;
+            if (PIT_DIM == 1) {
+              const u64 m = __ballot(bit);
+              if (ln == 0) {
+                atomicOr(&T[trl * 32], (uint32_t)m);
+                if (m >> 32) atomicOr(&T[trl * 32 + 1], (uint32_t)(m >> 32));
+              }
+            } else if (bit) {
+              atomicOr(&T[ln * 2 + (trl >> 5)], 1u << (trl & 31));
+            }
+          }
+        } else if (fl != 0) {
+          if (PIT_DIM == 1) {
+            atomicOr(&T[trl * 32 + ((ln * F) >> 5)], fl << ((ln * F) & 31));
+          } else {
+#pragma unroll
+            for (int q = 0; q < F; ++q)
+              if ((fl >> q) & 1u) atomicOr(&T[(ln * F + q) * 2 + (trl >> 5)], 1u << (trl & 31));
+          }
+        }
+        cur = make_uint4(0, 0, 0, 0);
+      }
+      if (rem == mt_rows) { rem = 0; ++trl; }
+    }
+  }
+  __syncthreads();
+
+  if (PIT_DIM == 1) {
+    const int row_end = min(rows, rblk + 64);
+    const int ntr = (row_end - 1) / mt_rows - tr_first + 1;
+    if (nb >= 32) {
+      const int nu = nb / 32;
+      // with direct stores the last strip also clears the padding of the segment's last word
+      const int nux = nu + ((direct && strip == (int)gridDim.x - 1) ? 2 : 0);
+      for (int i = tid; i < ntr * nux; i += 256) {
+        const int t = i / nux, j = i % nux;
+        const int64_t u = (int64_t)strip * nu + j;
+        if (u < 2 * (int64_t)W) {
+          const uint32_t val = j < nu ? T[t * 32 + j] : 0u;
+          uint32_t* p = words32 + (int64_t)(tr_first + t) * W * 2 + u;
+          if (direct) *p = val;
+          else if (val) atomicOr(p, val);
+        }
+      }
+    } else {
+      const int64_t bitpos = (int64_t)strip * nb;
+      for (int t = tid; t < ntr; t += 256) {
+        const uint32_t val = T[t * 32];
+        if (val) atomicOr(words32 + (int64_t)(tr_first + t) * W * 2 + (bitpos >> 5), val << (bitpos & 31));
+      }
+    }
+  } else {
+    for (int tc = tid; tc < nb; tc += 256) {
+      const int64_t seg = (int64_t)strip * nb + tc;
+      if (seg >= nseg) continue;
+      const uint32_t lo = T[tc * 2], hi = T[tc * 2 + 1];
+      if (direct) {      // mt_rows == 1: the 64 rows of this workgroup are one whole word
+        uint32_t* p = words32 + (seg * W + blockIdx.y) * 2;
+        *reinterpret_cast<uint2*>(p) = make_uint2(lo, hi);
+      } else {
+        const u64 x = (u64)lo | ((u64)hi << 32);
+        if (x == 0) continue;
+        const int w = tr_first >> 6, off = tr_first & 63;
+        const u64 a = x << off, b = off ? (x >> (64 - off)) : 0ull;
+        uint32_t* p = words32 + (seg * W + w) * 2;
+        if ((uint32_t)a) atomicOr(p, (uint32_t)a);
+        if (a >> 32) atomicOr(p + 1, (uint32_t)(a >> 32));
+        if ((uint32_t)b) atomicOr(p + 2, (uint32_t)b);
+        if (b >> 32) atomicOr(p + 3, (uint32_t)(b >> 32));
+      }
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
 // pass 1 for routing decisions: segment e, bit t  <=>  expert_id[t] == e
 // ----------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
@@ -179,17 +336,54 @@ k_bitmap_route(const int32_t* __restrict__ expert_id, int T, int E, int W, u64* 
 }
 
 // ----------------------------------------------------------------------------------------------
-// per-segment popcount (only used when there are many segments)
+// two-level counts (only used when there are many segments): cnt[s] = set bits of segment s,
+// blk[b] = set bits of segments 16 b .. 16 b + 15.  The start of segment s is then the sum of
+// blk[0 .. s / 16) and cnt[16 (s / 16) .. s): two short loads per workgroup instead of a scan pass.
 // ----------------------------------------------------------------------------------------------
+constexpr int SEG_BLK = 16;
+
 __global__ void __launch_bounds__(256)
-k_seg_count(const u64* __restrict__ words, int nseg, int W, int32_t* __restrict__ cnt) {
-  const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (s >= nseg) return;
-  int c = 0;
-  for (int w = lane_id(); w < W; w += 64) c += __popcll(words[(int64_t)s * W + w]);
+k_seg_count(const u64* __restrict__ words, int nseg, int W, int32_t* __restrict__ cnt, int32_t* __restrict__ blk) {
+  __shared__ int wsum[4];
+  const int wv = threadIdx.x >> 6, ln = lane_id();
+  int wave_total = 0;
+  const int s0 = blockIdx.x * SEG_BLK + wv * 4;
+  if (W <= 64) {       // one word per lane: the 4 segments of the wave are requested at once
+    u64 x[4];
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
-  if (lane_id() == 0) cnt[s] = c;
+    for (int j = 0; j < 4; ++j) x[j] = (s0 + j < nseg && ln < W) ? words[(int64_t)(s0 + j) * W + ln] : 0ull;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int c = __popcll(x[j]);
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
+      if (ln == 0 && s0 + j < nseg) cnt[s0 + j] = c;
+      wave_total += c;
+    }
+  } else {
+    for (int j = 0; j < 4; ++j) {
+      const int s = s0 + j;
+      if (s >= nseg) break;
+      int c = 0;
+      for (int w = ln; w < W; w += 64) c += __popcll(words[(int64_t)s * W + w]);
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
+      if (ln == 0) cnt[s] = c;
+      wave_total += c;
+    }
+  }
+  if (ln == 0) wsum[wv] = wave_total;
+  __syncthreads();
+  if (threadIdx.x == 0) blk[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+// this thread's share of the number of set bits ahead of segment s (sum over the workgroup = the start)
+__device__ __forceinline__ int seg_start_part(const int32_t* __restrict__ cnt, const int32_t* __restrict__ blk, int s,
+                                              int tid, int nthreads) {
+  int part = 0;
+  for (int i = tid; i < s / SEG_BLK; i += nthreads) part += blk[i];
+  for (int i = tid; i < s % SEG_BLK; i += nthreads) part += cnt[s - s % SEG_BLK + i];
+  return part;
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -204,8 +398,23 @@ __device__ __forceinline__ int block_sum_256(int v, int* sm) {
   return sm[0] + sm[1] + sm[2] + sm[3];
 }
 
+// this thread's share of the set bits of words[0 .. n): eight loads in flight per thread
+__device__ __forceinline__ int popcount_part(const u64* __restrict__ words, int64_t n, int tid) {
+  int part = 0;
+  int64_t i = tid;
+  for (; i + 7 * 256 < n; i += 8 * 256) {
+    u64 x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = words[i + j * 256];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part += __popcll(x[j]);
+  }
+  for (; i < n; i += 256) part += __popcll(words[i]);
+  return part;
+}
+
 __global__ void __launch_bounds__(256)
-k_emit(const u64* __restrict__ words, const int32_t* __restrict__ seg_cnt, const uint32_t* __restrict__ occ,
+k_emit(const u64* __restrict__ words, const int32_t* __restrict__ cnt, const int32_t* __restrict__ blk, const uint32_t* __restrict__ occ,
        int nseg, int npit, int W, int cap, int total_items,
        int32_t* __restrict__ seg_ptr, int32_t* __restrict__ idx, uint32_t* __restrict__ bits,
        int32_t* __restrict__ status) {
@@ -218,11 +427,10 @@ k_emit(const u64* __restrict__ words, const int32_t* __restrict__ seg_cnt, const
 
   // start of this segment = number of set bits in all earlier segments
   int part = 0;
-  if (seg_cnt) {
-    for (int i = tid; i < s; i += 256) part += seg_cnt[i];
+  if (cnt) {
+    part = seg_start_part(cnt, blk, s, tid, 256);
   } else {
-    const int64_t n = (int64_t)s * W;
-    for (int64_t i = tid; i < n; i += 256) part += __popcll(words[i]);
+    part = popcount_part(words, (int64_t)s * W, tid);
   }
   const int base = block_sum_256(part, red);
 
@@ -276,7 +484,7 @@ k_emit(const u64* __restrict__ words, const int32_t* __restrict__ seg_cnt, const
 constexpr int EMIT_CH = 16;
 
 __global__ void __launch_bounds__(256)
-k_emit_chunked(const u64* __restrict__ words, const int32_t* __restrict__ seg_cnt, const uint32_t* __restrict__ occ,
+k_emit_chunked(const u64* __restrict__ words, const int32_t* __restrict__ cnt, const int32_t* __restrict__ blk, const uint32_t* __restrict__ occ,
                int nseg, int npit, int W, int cap, int total_items,
                int32_t* __restrict__ seg_ptr, int32_t* __restrict__ idx, uint32_t* __restrict__ bits,
                int32_t* __restrict__ status) {
@@ -296,12 +504,11 @@ k_emit_chunked(const u64* __restrict__ words, const int32_t* __restrict__ seg_cn
   }
   // set bits ahead of this chunk: earlier segments, then the earlier words of this segment
   int part = 0;
-  if (seg_cnt) {
-    for (int i = tid; i < s; i += 256) part += seg_cnt[i];
-    for (int i = tid; i < w_first; i += 256) part += __popcll(words[row0 + i]);
+  if (cnt) {
+    part = seg_start_part(cnt, blk, s, tid, 256);
+    part += popcount_part(words + row0, w_first, tid);
   } else {
-    const int64_t n = row0 + w_first;
-    for (int64_t i = tid; i < n; i += 256) part += __popcll(words[i]);
+    part = popcount_part(words, row0 + w_first, tid);
   }
   const int base = block_sum_256(part, red);
 
@@ -335,6 +542,69 @@ k_emit_chunked(const u64* __restrict__ words, const int32_t* __restrict__ seg_cn
   }
 }
 
+// Same result for many short segments (at most 64 words each): one wave per segment, no LDS and no
+// barrier.  Lane w holds word w; empty words are skipped.
+__global__ void __launch_bounds__(256)
+k_emit_short(const u64* __restrict__ words, const int32_t* __restrict__ cnt, const int32_t* __restrict__ blk,
+             const uint32_t* __restrict__ occ, int nseg, int npit, int W, int cap, int total_items,
+             int32_t* __restrict__ seg_ptr, int32_t* __restrict__ idx, uint32_t* __restrict__ bits,
+             int32_t* __restrict__ status) {
+  const int ln = lane_id();
+  const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (s >= nseg) return;
+  const u64 word = ln < W ? words[(int64_t)s * W + ln] : 0ull;
+  int base = seg_start_part(cnt, blk, s, ln, 64);
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) base += __shfl_xor(base, d);
+  const int pc = __popcll(word);
+  int inc = pc;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(inc, d);
+    if (ln >= d) inc += t;
+  }
+  const int off = base + inc - pc;
+  const int total = __shfl(inc, 63);
+  int maxpc = pc;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) maxpc = max(maxpc, __shfl_xor(maxpc, d));
+  if (maxpc <= 8) {    // sparse segment: every lane walks the few set bits of its own word
+    u64 x = word;
+    int pos = off;
+    while (x) {
+      const int c = ln * 64 + __ffsll((long long)x) - 1;
+      x &= x - 1ull;
+      if (pos < cap) {
+        idx[pos] = c;
+        if (bits) bits[pos] = occ[(int64_t)s * npit + c];
+      }
+      ++pos;
+    }
+  }
+  u64 live = maxpc <= 8 ? 0ull : __ballot(word != 0ull);
+  while (live) {
+    const int i = __ffsll((long long)live) - 1;
+    live &= live - 1ull;
+    const u64 x = ((u64)(uint32_t)__shfl((int)(uint32_t)(word >> 32), i) << 32) | (u64)(uint32_t)__shfl((int)(uint32_t)word, i);
+    const int o = __shfl(off, i);
+    if ((x >> ln) & 1ull) {
+      const int pos = o + __popcll(x & ((1ull << ln) - 1ull));
+      const int c = i * 64 + ln;
+      if (pos < cap) {
+        idx[pos] = c;
+        if (bits) bits[pos] = occ[(int64_t)s * npit + c];
+      }
+    }
+  }
+  if (ln == 0) {
+    seg_ptr[s] = base;
+    if (s == nseg - 1) {
+      seg_ptr[nseg] = base + total;
+      if (status) *status = total_items - (base + total);
+    }
+  }
+}
+
 // total number of set bits of the bitmap (CoverAlgo): one atomic per workgroup into a zeroed counter
 __global__ void __launch_bounds__(256)
 k_count_bits(const u64* __restrict__ words, int64_t nwords, int32_t* __restrict__ count) {
@@ -364,15 +634,19 @@ Layout make_layout(int rows, int cols, int mt_rows, int mt_cols, int pit_dim, in
   L.W = (L.npit + 63) / 64;
   L.words_bytes = (size_t)L.nseg * L.W * 8;
   L.occ_bytes = want_bits ? (((size_t)L.nseg * L.npit * 4 + 15) & ~(size_t)15) : 0;
-  L.cnt_bytes = ((size_t)L.nseg * 4 + 15) & ~(size_t)15;
+  L.cnt_bytes = (((size_t)L.nseg + (size_t)(L.nseg + SEG_BLK - 1) / SEG_BLK) * 4 + 15) & ~(size_t)15;   // cnt[nseg], blk[ceil(nseg / SEG_BLK)]
   return L;
 }
 
-// k_emit_chunked serves segments of up to 1024 words (segment number in the grid's y), k_emit (one
-// workgroup per segment) the rest.
+// k_emit_short (one wave per segment) serves many segments of at most 64 words, k_emit_chunked
+// segments of up to 1024 words (segment number in the grid's y), k_emit (one workgroup per segment)
+// the rest.
+inline bool use_short_emit(const Layout& L) { return L.W <= 64 && L.nseg >= 1024; }
 inline bool use_chunked_emit(const Layout& L) { return L.W <= 1024 && L.nseg <= 65535; }
-// many earlier words per workgroup => precompute per-segment counts in a separate launch
-inline bool use_seg_count(const Layout& L) { return (int64_t)L.nseg * L.W > (use_chunked_emit(L) ? 16384 : 65536); }
+// many earlier words per workgroup => two-level per-segment counts in a launch of their own
+inline bool use_seg_count(const Layout& L) {
+  return use_short_emit(L) || (int64_t)L.nseg * L.W > (use_chunked_emit(L) ? 16384 : 65536);
+}
 
 int launch_emit(const Layout& L, const u64* words, int32_t* cnt, const uint32_t* occ, const pit_index* out,
                 int total_items, int32_t* status, hipStream_t st) {
@@ -387,18 +661,24 @@ int launch_emit(const Layout& L, const u64* words, int32_t* cnt, const uint32_t*
     return PIT_OK;
   }
   const int32_t* cnt_arg = nullptr;
+  const int32_t* blk_arg = nullptr;
   if (use_seg_count(L)) {
-    hipLaunchKernelGGL(k_seg_count, dim3((L.nseg + 3) / 4), dim3(256), 0, st, words, L.nseg, L.W, cnt);
+    int32_t* blk = cnt + L.nseg;
+    hipLaunchKernelGGL(k_seg_count, dim3((L.nseg + SEG_BLK - 1) / SEG_BLK), dim3(256), 0, st, words, L.nseg, L.W, cnt, blk);
     PIT_LAUNCH_CHECK();
     cnt_arg = cnt;
+    blk_arg = blk;
   }
-  if (use_chunked_emit(L)) {
+  if (use_short_emit(L)) {
+    hipLaunchKernelGGL(k_emit_short, dim3((L.nseg + 3) / 4), dim3(256), 0, st, words, cnt_arg, blk_arg, occ, L.nseg,
+                       L.npit, L.W, out->cap, total_items, out->seg_ptr, out->idx, out->bits, status);
+  } else if (use_chunked_emit(L)) {
     hipLaunchKernelGGL(k_emit_chunked, dim3((unsigned)ceil_div(L.W, EMIT_CH), (unsigned)L.nseg), dim3(256), 0, st,
-                       words, cnt_arg, occ, L.nseg, L.npit, L.W, out->cap, total_items, out->seg_ptr, out->idx,
+                       words, cnt_arg, blk_arg, occ, L.nseg, L.npit, L.W, out->cap, total_items, out->seg_ptr, out->idx,
                        out->bits, status);
   } else {
-    hipLaunchKernelGGL(k_emit, dim3(L.nseg), dim3(256), 0, st, words, cnt_arg, occ, L.nseg, L.npit, L.W, out->cap,
-                       total_items, out->seg_ptr, out->idx, out->bits, status);
+    hipLaunchKernelGGL(k_emit, dim3(L.nseg), dim3(256), 0, st, words, cnt_arg, blk_arg, occ, L.nseg, L.npit, L.W,
+                       out->cap, total_items, out->seg_ptr, out->idx, out->bits, status);
   }
   PIT_LAUNCH_CHECK();
   return PIT_OK;
@@ -408,6 +688,56 @@ int launch_emit(const Layout& L, const u64* words, int32_t* cnt, const uint32_t*
 }  // namespace pit
 
 using namespace pit;
+
+// fast path C serves power-of-two micro-tile widths up to 1 KiB on 16-byte aligned rows
+static bool tiles_path_ok(const Layout& L, int esize, int rows, int64_t row_bytes, int64_t mt_bytes, bool vec_ok) {
+  return vec_ok && mt_bytes <= 1024 && (mt_bytes & (mt_bytes - 1)) == 0 && rows <= 65535 * 64 &&
+         (int64_t)L.nseg * L.W * 2 < (1ll << 31) && esize <= mt_bytes;
+}
+
+template <int ESIZE, int F>
+static void launch_tiles_ef(int pit_dim, dim3 grid, hipStream_t st, const void* src, int64_t ld_bytes, int rows,
+                            int row_bytes, int mt_rows, int lpm, int nseg, int W, int direct, uint32_t* words32) {
+  if (pit_dim == 0)
+    hipLaunchKernelGGL((k_bitmap_tiles<ESIZE, F, 0>), grid, dim3(256), 0, st, src, ld_bytes, rows, row_bytes, mt_rows, lpm, nseg, W, direct, words32);
+  else
+    hipLaunchKernelGGL((k_bitmap_tiles<ESIZE, F, 1>), grid, dim3(256), 0, st, src, ld_bytes, rows, row_bytes, mt_rows, lpm, nseg, W, direct, words32);
+}
+
+template <int ESIZE>
+static void launch_tiles_e(int f, int pit_dim, dim3 grid, hipStream_t st, const void* src, int64_t ld_bytes, int rows,
+                           int row_bytes, int mt_rows, int lpm, int nseg, int W, int direct, uint32_t* words32) {
+#define PIT_TILES_CASE(FF) launch_tiles_ef<ESIZE, FF>(pit_dim, grid, st, src, ld_bytes, rows, row_bytes, mt_rows, lpm, nseg, W, direct, words32)
+  if (f == 1) PIT_TILES_CASE(1);
+  else if (f == 2) PIT_TILES_CASE(2);
+  else if (f == 4) PIT_TILES_CASE(4);
+  else if constexpr (ESIZE <= 2) {      // f <= 16 / ESIZE
+    if (f == 8) PIT_TILES_CASE(8);
+    else if constexpr (ESIZE == 1) PIT_TILES_CASE(16);
+  }
+#undef PIT_TILES_CASE
+}
+
+static int launch_bitmap_tiles(const Layout& L, const void* d_src, int esize, int rows, int row_bytes, int64_t ld_bytes,
+                               int mt_rows, int mt_bytes, int pit_dim, u64* words, hipStream_t st) {
+  const int f = mt_bytes >= 16 ? 1 : 16 / mt_bytes;
+  const int lpm = mt_bytes >= 16 ? mt_bytes / 16 : 1;
+  const int nb = f == 1 ? 64 / lpm : 64 * f;
+  // a workgroup (64 rows x 1 KiB) owns whole units of the bitmap in these cases only
+  const int direct = pit_dim == 0 ? (mt_rows == 1) : (64 % mt_rows == 0 && nb % 32 == 0);
+  uint32_t* words32 = reinterpret_cast<uint32_t*>(words);
+  if (!direct) {
+    const int n = (int)((int64_t)L.nseg * L.W * 2);
+    hipLaunchKernelGGL(k_fill_i32, dim3((n + 255) / 256), dim3(256), 0, st, reinterpret_cast<int32_t*>(words32), n, 0);
+    PIT_LAUNCH_CHECK();
+  }
+  dim3 grid((unsigned)ceil_div(row_bytes, 1024), (unsigned)ceil_div(rows, 64));
+  if (esize == 1)      launch_tiles_e<1>(f, pit_dim, grid, st, d_src, ld_bytes, rows, row_bytes, mt_rows, lpm, L.nseg, L.W, direct, words32);
+  else if (esize == 2) launch_tiles_e<2>(f, pit_dim, grid, st, d_src, ld_bytes, rows, row_bytes, mt_rows, lpm, L.nseg, L.W, direct, words32);
+  else                 launch_tiles_e<4>(f, pit_dim, grid, st, d_src, ld_bytes, rows, row_bytes, mt_rows, lpm, L.nseg, L.W, direct, words32);
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
+}
 
 // pass 1: the bitmap of non-empty micro-tiles (and, if occ != nullptr, their element occupancy)
 static int launch_bitmap(const Layout& L, const void* d_src, int esize, int rows, int cols, int64_t ld,
@@ -423,6 +753,8 @@ static int launch_bitmap(const Layout& L, const void* d_src, int esize, int rows
     if (esize == 1)      hipLaunchKernelGGL(k_bitmap_rows<1>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
     else if (esize == 2) hipLaunchKernelGGL(k_bitmap_rows<2>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
     else                 hipLaunchKernelGGL(k_bitmap_rows<4>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
+  } else if (want_bits == false && tiles_path_ok(L, esize, rows, row_bytes, mt_bytes, vec_ok)) {
+    return launch_bitmap_tiles(L, d_src, esize, rows, (int)row_bytes, ld * esize, mt_rows, (int)mt_bytes, pit_dim, words, st);
   } else if (pit_dim == 1 && mt_cols == 1 && esize == 1 && vec_ok && cols % 16 == 0) {
     const int chunks = (L.W * 64 + 1023) / 1024;
     const int64_t waves = (int64_t)L.nseg * chunks;

@@ -81,6 +81,50 @@ def test_shapes_and_paths(pit, shape, mt, pit_dim, dtype):
     _check(pit, src, mt[0], mt[1], pit_dim, want_bits=False)
 
 
+def _tile_cases():
+    out = []
+    for dtype, es in ((np.uint8, 1), (np.float16, 2), (np.float32, 4)):
+        for mt_bytes in (1, 2, 4, 8, 16, 32, 64, 256, 1024):
+            if mt_bytes < es:
+                continue
+            mt_cols = mt_bytes // es
+            for mt_rows in (1, 2, 3, 16, 24, 64, 80):
+                # rows: several 64-row blocks with a ragged tail; row bytes: two strips and a ragged third
+                rows = mt_rows * max(1, 200 // mt_rows)
+                row_bytes = max(mt_bytes, 16) * max(1, 2064 // max(mt_bytes, 16))
+                if mt_bytes == 1024:
+                    row_bytes = 3072
+                out.append((rows, row_bytes // es, mt_rows, mt_cols, dtype))
+    return out
+
+
+@pytest.mark.parametrize("rows,cols,mt_rows,mt_cols,dtype", _tile_cases())
+def test_vector_path_for_any_micro_tile(pit, rows, cols, mt_rows, mt_cols, dtype):
+    """Power-of-two micro-tile widths from one byte to 1 KiB, heights that divide, straddle and exceed the
+    64-row block of a workgroup, both PIT dimensions."""
+    g = np.random.default_rng(rows * 7919 + cols * 31 + mt_rows)
+    src = ((g.random((rows, cols)) < 0.02) * (1 + g.random((rows, cols)))).astype(dtype)
+    if dtype != np.uint8:
+        src[g.random((rows, cols)) < 0.01] = -0.0       # negative zero is zero
+    _check(pit, src, mt_rows, mt_cols, 0)
+    _check(pit, src, mt_rows, mt_cols, 1)
+
+
+def test_vector_path_dense_and_strided(pit):
+    g = np.random.default_rng(11)
+    full = (1 + g.random((192, 1088))).astype(np.float16)
+    for mt in ((1, 1), (2, 4), (32, 8), (48, 64)):
+        _check(pit, full, mt[0], mt[1], 0)
+        _check(pit, full, mt[0], mt[1], 1)
+    big = np.zeros((130, 4096), dtype=np.uint8)
+    sub = big[:, 1024:3104]                    # ld = 4096, 2080 columns, 16-byte aligned start
+    sub[g.integers(0, 130, 300), g.integers(0, 2080, 300)] = 7
+    t = to_dev(big)[:, 1024:3104]
+    for mt in ((1, 1), (2, 2), (10, 16), (26, 32), (130, 4)):
+        _check(pit, np.ascontiguousarray(sub), mt[0], mt[1], 0, src_t=t)
+        _check(pit, np.ascontiguousarray(sub), mt[0], mt[1], 1, src_t=t)
+
+
 def test_strided_view_and_special_values(pit):
     g = np.random.default_rng(3)
     big = np.zeros((64, 256), dtype=np.float16)
@@ -115,9 +159,15 @@ def test_many_segments_path(pit):
     """1x1 granularity on 4096 x 4096 (Section 5.4's shape): 4096 segments, separate count pass."""
     m = wl.iid_block_mask(4096, 4096, 1, 1, 0.95, seed=1)
     _check(pit, m, 1, 1, 0)
+    _check(pit, m, 1, 1, 1)
     m32 = wl.iid_block_mask(4096, 4096, 32, 32, 0.9, seed=2)
     _check(pit, m32, 32, 32, 1)
+    _check(pit, m32, 32, 32, 0)
     _check(pit, m32, 16, 16, 0)
+    h = (wl.iid_block_mask(4096, 4096, 32, 64, 0.9, seed=3) * 1.5).astype(np.float16)
+    _check(pit, h, 32, 64, 0)
+    _check(pit, h, 32, 64, 1)
+    _check(pit, h, 1, 1, 1)
 
 
 def test_repeatable(pit):
