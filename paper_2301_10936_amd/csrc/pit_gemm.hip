@@ -448,8 +448,9 @@ k_gather_m(const GemmArgs g) {
 // exactly once per workgroup and never through LDS.
 // The four wavefronts split the tile's k-list in slabs of 32 entries (wave w takes slabs w, w+4, ..),
 // each accumulating a full 128 x 128 partial tile in 256 accumulator registers; at the end the
-// partial tiles are reduce-scattered through LDS (3 rounds of 64 KiB) and every wave stores a
-// quarter of the tile, 512 contiguous bytes per row.
+// partial tiles are reduce-scattered through LDS (4 rounds of 48 KiB) and every wave stores a
+// quarter of the tile, 512 contiguous bytes per row.  With more tiles than compute units a workgroup
+// loops over tiles.
 // The k loop is branch-free: list positions past the end are clamped to the last entry on load, the
 // last slab of each wave is processed apart with the clamped rows zeroed.
 // ------------------------------------------------------------------------------------------------
@@ -484,20 +485,27 @@ __device__ __forceinline__ void red_send(const f32x4_t (&acc)[8][8], PIT_LDS cha
 #pragma unroll
     for (int jb = 0; jb < 8; ++jb) *(PIT_LDS f32x4_t*)(slot + (a * 8 + jb) * 1024) = acc[2 * P + a][jb];
 }
-// Wave P adds the three other waves' partial sums and stores its quarter of the tile: rows
-// 32 * (lane / 16) + 8 e + ja; a lane holds 8 consecutive columns of such a row (one per jb), so 16
-// lanes write 512 (fp32) or 256 contiguous bytes.
-template <bool BF, int CT, int P>
-__device__ __forceinline__ void red_recv_store(f32x4_t (&acc)[8][8], PIT_LDS char* buf, const GemmArgs& g,
-                                               int m_base, int n0, int lane) {
+// Wave P adds the three other waves' partial sums to its own.
+template <int P>
+__device__ __forceinline__ void red_recv(f32x4_t (&acc)[8][8], PIT_LDS char* buf, int lane) {
+  // (all 16 reads of one sender are issued before the first addition: one LDS latency per sender
+  // instead of one per read)
 #pragma unroll
   for (int o = 1; o < 4; ++o) {
     PIT_LDS char* slot = buf + ((P + o) & 3) * RED_SLOT_BYTES + lane * 16;
+    f32x4_t part[16];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int i = 0; i < 16; ++i) part[i] = *(PIT_LDS f32x4_t*)(slot + i * 1024);
+    PIT_SCHED_FENCE();
 #pragma unroll
-      for (int jb = 0; jb < 8; ++jb) acc[2 * P + a][jb] += *(PIT_LDS f32x4_t*)(slot + (a * 8 + jb) * 1024);
+    for (int i = 0; i < 16; ++i) acc[2 * P + (i >> 3)][i & 7] += part[i];
+    PIT_SCHED_FENCE();
   }
+}
+// Wave P stores its quarter of the tile: rows 32 * (lane / 16) + 8 e + ja; a lane holds 8
+// consecutive columns of such a row (one per jb), so 16 lanes write 512 (fp32) or 256 contiguous bytes.
+template <bool BF, int CT, int P>
+__device__ __forceinline__ void red_store(const f32x4_t (&acc)[8][8], const GemmArgs& g, int m_base, int n0, int lane) {
   const int q = lane & 15, kb = lane >> 4;
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
@@ -507,49 +515,84 @@ __device__ __forceinline__ void red_recv_store(f32x4_t (&acc)[8][8], PIT_LDS cha
       const int64_t row = m_base + 32 * kb + 8 * e + ja;
       const int col = n0 + 8 * q;
       if constexpr (CT == 0) {
-        float* d = reinterpret_cast<float*>(g.C) + row * g.ldc + col;
-        *reinterpret_cast<float4*>(d)     = make_float4(acc[ja][0][e], acc[ja][1][e], acc[ja][2][e], acc[ja][3][e]);
-        *reinterpret_cast<float4*>(d + 4) = make_float4(acc[ja][4][e], acc[ja][5][e], acc[ja][6][e], acc[ja][7][e]);
+        // (streaming stores: the result is not read again by this kernel and should not displace the
+        // operand panels from L2)
+        typedef float f4_t __attribute__((ext_vector_type(4)));
+        f4_t* d = reinterpret_cast<f4_t*>(reinterpret_cast<float*>(g.C) + row * g.ldc + col);
+        __builtin_nontemporal_store(f4_t{acc[ja][0][e], acc[ja][1][e], acc[ja][2][e], acc[ja][3][e]}, d);
+        __builtin_nontemporal_store(f4_t{acc[ja][4][e], acc[ja][5][e], acc[ja][6][e], acc[ja][7][e]}, d + 1);
       } else {
         uint32_t w[4];
 #pragma unroll
         for (int x = 0; x < 4; ++x)
           w[x] = (uint32_t)f32_to_in<BF>(acc[ja][2 * x][e]) | ((uint32_t)f32_to_in<BF>(acc[ja][2 * x + 1][e]) << 16);
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(g.C) + row * g.ldc + col) = make_uint4(w[0], w[1], w[2], w[3]);
+        __builtin_nontemporal_store(u32x4_t{w[0], w[1], w[2], w[3]},
+                                    reinterpret_cast<u32x4_t*>(reinterpret_cast<uint16_t*>(g.C) + row * g.ldc + col));
       }
     }
   }
 }
 
+// what a wave needs to know about one tile
+struct DirectTile {
+  int seg, n0, list_len, n_w;      // tile row (= index segment), first column, length of the k-list, this wave's slabs
+  const char* list;                // the k-list
+  uint32_t a_col, b_col;           // this lane's byte offsets into a row of At and of B
+};
+
 template <bool BF, int CT>
 __global__ void __launch_bounds__(256)
-k_gather_k_direct(const GemmArgs g) {
+k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
   constexpr int SK = 32;   // list entries per slab = k extent of one MFMA
   __shared__ __attribute__((aligned(16))) char s_red[2 * RED_BUF_BYTES];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q = lane & 15, kb = lane >> 4;
+  const char* a_src = uniform_ptr(g.A);
+  const char* b_src = uniform_ptr(g.B);
+  const uint32_t pitch_a = (uint32_t)(g.lda * 2), pitch_b = (uint32_t)(g.ldb * 2);
 
+  // The grid is one-dimensional and may hold fewer workgroups than there are tiles: a workgroup then
+  // works through tiles lin = blockIdx.x, blockIdx.x + gridDim.x, ... (gridDim.x is a multiple of 8
+  // in that case, so all of them belong to the same XCD).
+  const int tn = g.N / TN, total = tn * tm_tiles;
   // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that each
   // XCD works on a contiguous run of tiles, ordered in bands of 4 tile rows x all tile columns.
-  int tile_row, tile_col;
-  {
-    const int tn = gridDim.x, tm = gridDim.y, total = tn * tm;
-    const int lin = blockIdx.x + tn * blockIdx.y;
+  auto tile_of = [&](int lin) -> DirectTile {
     const int x = lin & 7, qq = total >> 3, rr = total & 7;
     const int lp = x * qq + min(x, rr) + (lin >> 3);
     constexpr int GM = 4;
     const int band = lp / (GM * tn), within = lp - band * (GM * tn);
-    const int rows = min(GM, tm - band * GM);
-    tile_row = band * GM + within % rows;
-    tile_col = within / rows;
-  }
-  const int n0 = tile_col * TN;
-  const int seg = tile_row;
-  const int list_begin = g.seg_ptr[seg];
-  const int list_len = g.seg_ptr[seg + 1] - list_begin;
-  const int nslab = (list_len + SK - 1) / SK;
-  const int n_w = nslab > wv ? (nslab - wv + 3) >> 2 : 0;   // this wave's slabs: wv, wv + 4, ...
+    const int rows = min(GM, tm_tiles - band * GM);
+    DirectTile t;
+    t.seg = band * GM + within % rows;
+    t.n0 = (within / rows) * TN;
+    const int list_begin = g.seg_ptr[t.seg];
+    t.list_len = g.seg_ptr[t.seg + 1] - list_begin;
+    const int nslab = (t.list_len + SK - 1) / SK;
+    t.n_w = nslab > wv ? (nslab - wv + 3) >> 2 : 0;   // this wave's slabs: wv, wv + 4, ...
+    t.list = uniform_ptr(g.idx + list_begin);
+    t.a_col = (uint32_t)(t.seg * TM + 8 * q) * 2u;
+    t.b_col = (uint32_t)(t.n0 + 8 * q) * 2u;
+    return t;
+  };
+
+  // lane l of a slab's list load holds entry (l % 32) of the slab
+  auto load_list = [&](const DirectTile& T, int t) -> int {
+    const int pos = min(SK * (wv + 4 * t) + (lane & 31), T.list_len - 1);
+    typedef const int __attribute__((address_space(1))) * gint_t;
+    return *(gint_t)(uintptr_t)(reinterpret_cast<uintptr_t>(T.list) + (uint32_t)pos * 4u);
+  };
+  // rows k(8 kb + i), i = 0..7, of At and of B
+  auto issue = [&](const DirectTile& T, int kraw, uint4 (&ra)[8], uint4 (&rb)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t k = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * kb + i) * 4, kraw);
+      ra[i] = load16(a_src, __umul24(k, pitch_a) + T.a_col);
+      rb[i] = load16(b_src, __umul24(k, pitch_b) + T.b_col);
+    }
+  };
 
   f32x4_t acc[8][8];
 #pragma unroll
@@ -557,28 +600,6 @@ k_gather_k_direct(const GemmArgs g) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int q = lane & 15, kb = lane >> 4;
-  const char* a_src = uniform_ptr(g.A);
-  const char* b_src = uniform_ptr(g.B);
-  const char* list = uniform_ptr(g.idx + list_begin);
-  const uint32_t pitch_a = (uint32_t)(g.lda * 2), pitch_b = (uint32_t)(g.ldb * 2);
-  const uint32_t a_col = (uint32_t)(seg * TM + 8 * q) * 2u, b_col = (uint32_t)(n0 + 8 * q) * 2u;
-
-  // lane l of a slab's list load holds entry (l % 32) of the slab
-  auto load_list = [&](int t) -> int {
-    const int pos = min(SK * (wv + 4 * t) + (lane & 31), list_len - 1);
-    typedef const int __attribute__((address_space(1))) * gint_t;
-    return *(gint_t)(uintptr_t)(reinterpret_cast<uintptr_t>(list) + (uint32_t)pos * 4u);
-  };
-  // rows k(8 kb + i), i = 0..7, of At and of B
-  auto issue = [&](int kraw, uint4 (&ra)[8], uint4 (&rb)[8]) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint32_t k = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * kb + i) * 4, kraw);
-      ra[i] = load16(a_src, __umul24(k, pitch_a) + a_col);
-      rb[i] = load16(b_src, __umul24(k, pitch_b) + b_col);
-    }
-  };
   // 64 MFMAs on one slab.  All B operands are transposed first; the A operand of column group
   // ja + 1 is transposed (4 v_perm_b32) in the shadow of the first MFMAs of group ja.  The order is
   // pinned: an MFMA must not read a register in the issue slot right after a vector instruction
@@ -589,7 +610,7 @@ k_gather_k_direct(const GemmArgs g) {
   // once the B operands are transposed), the A rows during group 7 (ra is dead once the last A
   // operand is transposed).  Spreading them keeps 16 to 24 loads of a wave in flight; with 32 in
   // flight at once the load path of a CU runs at less than half its rate (measured).
-  auto process_impl = [&](uint4 (&ra)[8], uint4 (&rb)[8], int kraw, auto issue_tag) {
+  auto process_impl = [&](const DirectTile& T, uint4 (&ra)[8], uint4 (&rb)[8], int kraw, auto issue_tag) {
     constexpr bool ISSUE = decltype(issue_tag)::value;
     uint4 bfr[8];
 #pragma unroll
@@ -614,9 +635,9 @@ k_gather_k_direct(const GemmArgs g) {
         if constexpr (ISSUE) {
           if (ja < 4 && (jb == 4 || jb == 6)) {
             const int i = ja * 2 + ((jb - 4) >> 1);
-            rb[i] = load16(b_src, __umul24(kk[i], pitch_b) + b_col);
+            rb[i] = load16(b_src, __umul24(kk[i], pitch_b) + T.b_col);
           }
-          if (ja == 7) ra[jb] = load16(a_src, __umul24(kk[jb], pitch_a) + a_col);
+          if (ja == 7) ra[jb] = load16(a_src, __umul24(kk[jb], pitch_a) + T.a_col);
         }
         PIT_SCHED_FENCE();
       }
@@ -624,57 +645,66 @@ k_gather_k_direct(const GemmArgs g) {
       for (int jj = 0; jj < 4; ++jj) af[jj] = afn[jj];
     }
   };
-  auto process = [&](uint4 (&ra)[8], uint4 (&rb)[8]) { process_impl(ra, rb, 0, std::false_type{}); };
-  auto process_issue = [&](uint4 (&ra)[8], uint4 (&rb)[8], int kraw) { process_impl(ra, rb, kraw, std::true_type{}); };
+  auto process = [&](const DirectTile& T, uint4 (&ra)[8], uint4 (&rb)[8]) { process_impl(T, ra, rb, 0, std::false_type{}); };
+  auto process_issue = [&](const DirectTile& T, uint4 (&ra)[8], uint4 (&rb)[8], int kraw) { process_impl(T, ra, rb, kraw, std::true_type{}); };
   // local slab t with the rows of positions past the end of the list zeroed
-  auto process_last = [&](int t, uint4 (&ra)[8], uint4 (&rb)[8]) {
+  auto process_last = [&](const DirectTile& T, int t, uint4 (&ra)[8], uint4 (&rb)[8]) {
     const int p0 = SK * (wv + 4 * t) + 8 * kb;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      if (p0 + i >= list_len) { ra[i] = make_uint4(0, 0, 0, 0); rb[i] = make_uint4(0, 0, 0, 0); }
-    process(ra, rb);
+      if (p0 + i >= T.list_len) { ra[i] = make_uint4(0, 0, 0, 0); rb[i] = make_uint4(0, 0, 0, 0); }
+    process(T, ra, rb);
   };
 
-  if (n_w > 0) {
-    uint4 ra0[8], rb0[8], ra1[8], rb1[8];
-    // (the fences keep the list loads of slabs 2 and 3 ahead of the second slab's data loads: the
-    // memory counter retires in order, so a list load issued last would make the loop wait for all)
-    int k0 = load_list(0), k1 = load_list(1);
-    PIT_SCHED_FENCE();
-    issue(k0, ra0, rb0); k0 = load_list(2); PIT_SCHED_FENCE();
-    issue(k1, ra1, rb1); k1 = load_list(3); PIT_SCHED_FENCE();
-    int t = 0;
-    for (; t + 2 < n_w; t += 2) {
-      process_issue(ra0, rb0, k0); k0 = load_list(t + 4); PIT_SCHED_FENCE();
-      process_issue(ra1, rb1, k1); k1 = load_list(t + 5); PIT_SCHED_FENCE();
-    }
-    if (n_w - t == 2) {
-      process(ra0, rb0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) { ra0[i] = ra1[i]; rb0[i] = rb1[i]; }
-      ++t;
-    }
-    process_last(t, ra0, rb0);
-    PIT_MFMA_DRAIN();
-  }
-
-  // Reduction across the four waves, one quarter of the tile rows per round, double-buffered in
-  // LDS: round P's partial sums are written before barrier P and read by wave P after it, while the
-  // other waves already write round P + 1 into the other buffer.
+  uint4 ra0[8], rb0[8], ra1[8], rb1[8];
   PIT_LDS char* red = (PIT_LDS char*)s_red;
-  const int m_base = seg * TM;
-  if (wv != 0) red_send<0>(acc, red, wv, lane);
-  __syncthreads();
-  if (wv == 0) red_recv_store<BF, CT, 0>(acc, red, g, m_base, n0, lane);
-  if (wv != 1) red_send<1>(acc, red + RED_BUF_BYTES, wv, lane);
-  __syncthreads();
-  if (wv == 1) red_recv_store<BF, CT, 1>(acc, red + RED_BUF_BYTES, g, m_base, n0, lane);
-  if (wv != 2) red_send<2>(acc, red, wv, lane);
-  __syncthreads();
-  if (wv == 2) red_recv_store<BF, CT, 2>(acc, red, g, m_base, n0, lane);
-  if (wv != 3) red_send<3>(acc, red + RED_BUF_BYTES, wv, lane);
-  __syncthreads();
-  if (wv == 3) red_recv_store<BF, CT, 3>(acc, red + RED_BUF_BYTES, g, m_base, n0, lane);
+  for (int lin = blockIdx.x; lin < total; lin += gridDim.x) {
+    const DirectTile T = tile_of(lin);
+    if (T.n_w > 0) {
+      // (the fences keep the list loads of slabs 2 and 3 ahead of the second slab's data loads: the
+      // memory counter retires in order, so a list load issued last would make the loop wait for all)
+      int k0 = load_list(T, 0), k1 = load_list(T, 1);
+      PIT_SCHED_FENCE();
+      issue(T, k0, ra0, rb0); k0 = load_list(T, 2); PIT_SCHED_FENCE();
+      issue(T, k1, ra1, rb1); k1 = load_list(T, 3); PIT_SCHED_FENCE();
+      int t = 0;
+      for (; t + 2 < T.n_w; t += 2) {
+        process_issue(T, ra0, rb0, k0); k0 = load_list(T, t + 4); PIT_SCHED_FENCE();
+        process_issue(T, ra1, rb1, k1); k1 = load_list(T, t + 5); PIT_SCHED_FENCE();
+      }
+      if (T.n_w - t == 2) {
+        process(T, ra0, rb0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { ra0[i] = ra1[i]; rb0[i] = rb1[i]; }
+        ++t;
+      }
+      process_last(T, t, ra0, rb0);
+      PIT_MFMA_DRAIN();
+    }
+
+    // Reduction across the four waves, one quarter of the tile rows per round, double-buffered in
+    // LDS: round P's partial sums are written before barrier P and read by wave P after it, while the
+    // other waves already write round P + 1 into the other buffer.
+    const int m_base = T.seg * TM;
+    if (wv != 0) red_send<0>(acc, red, wv, lane);
+    __syncthreads();
+    if (wv == 0) { red_recv<0>(acc, red, lane); red_store<BF, CT, 0>(acc, g, m_base, T.n0, lane); }
+    if (wv != 1) red_send<1>(acc, red + RED_BUF_BYTES, wv, lane);
+    __syncthreads();
+    if (wv == 1) { red_recv<1>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 1>(acc, g, m_base, T.n0, lane); }
+    if (wv != 2) red_send<2>(acc, red, wv, lane);
+    __syncthreads();
+    if (wv == 2) { red_recv<2>(acc, red, lane); red_store<BF, CT, 2>(acc, g, m_base, T.n0, lane); }
+    if (wv != 3) red_send<3>(acc, red + RED_BUF_BYTES, wv, lane);
+    __syncthreads();
+    if (wv == 3) { red_recv<3>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 3>(acc, g, m_base, T.n0, lane); }
+    if (lin + (int)gridDim.x >= total) break;
+    PIT_SCHED_FENCE();
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
 }
 
 // Zero rows of C that no index entry names (single-segment GATHER_M): the list is ascending, so a
@@ -709,11 +739,27 @@ __global__ void __launch_bounds__(256) k_zero_rows(void* C, int64_t ld_bytes, in
 
 }  // namespace
 
+// compute units of the current device rounded down to a multiple of 8 (one share per XCD)
+static int compute_units() {
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cached[dev] = n & ~7;
+  }
+  return cached[dev];
+}
+
 template <bool BF, bool GK, int EPI, int CT>
 static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
   if constexpr (GK) {
     static_assert(EPI == EPI_STORE, "GATHER_K has the plain store epilogue only");
-    hipLaunchKernelGGL((k_gather_k_direct<BF, CT>), grid, dim3(256), 0, st, g);
+    // one workgroup fits on a compute unit: with more tiles than compute units the workgroups loop
+    const int total = (int)(grid.x * grid.y), cus = compute_units();
+    const unsigned wgs = (unsigned)(total <= cus ? total : cus);
+    hipLaunchKernelGGL((k_gather_k_direct<BF, CT>), dim3(wgs), dim3(256), 0, st, g, (int)grid.y);
     PIT_LAUNCH_CHECK();
     return PIT_OK;
   } else {

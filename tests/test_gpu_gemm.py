@@ -104,6 +104,38 @@ def test_gather_k_list_lengths_around_slab_boundaries(pit, live):
     assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(xb, wb))
 
 
+@pytest.mark.parametrize("tiles_m,tiles_n", [(24, 12), (9, 57), (65, 8)])
+def test_gather_k_more_tiles_than_compute_units(pit, tiles_m, tiles_n):
+    """More 128 x 128 tiles than the GPU has compute units: workgroups loop over tiles (accumulators
+    and reduction buffers are reused from tile to tile).  Segment lengths differ from tile row
+    to tile row (empty, shorter than one slab, waves without work, many slabs), so consecutive
+    tiles of a workgroup mix all cases."""
+    g = np.random.default_rng(tiles_m * 100 + tiles_n)
+    K, M, N = 300, 128 * tiles_m, 128 * tiles_n
+    lengths = [0, 1, 31, 32, 33, 64, 97, 128, 129, 200, 256, 300]
+    Xt = np.zeros((K, M), dtype=np.float32)
+    for s in range(tiles_m):
+        live = lengths[(s * 5 + tiles_n) % len(lengths)]
+        if live == 0:
+            continue
+        rows = np.sort(g.choice(K, size=live, replace=False))
+        Xt[rows, 128 * s:128 * (s + 1)] = g.integers(-3, 4, size=(live, 128))
+        Xt[rows, 128 * s] = 1.0                                           # keep the listed rows non-zero
+    W = g.integers(-3, 4, size=(K, N)).astype(np.float32)
+    xb, wb = wl.to_bf16_bits(Xt), wl.to_bf16_bits(W)
+    tX, tW = to_dev(xb), to_dev(wb)
+    ix = pit.pit_build_index(tX, 1, 128, 0)
+    C = torch.full((M, N), 7.0, device=dev())
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K, out=C)
+    torch.cuda.synchronize()
+    assert_index_equal(ix, orc.build_index(xb, 1, 128, 0))
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(xb, wb))
+    # twice in a row on the same output: nothing of the first call may leak into the second
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K, out=C)
+    torch.cuda.synchronize()
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(xb, wb))
+
+
 def test_gather_k_strided_operands_and_large_last_row(pit):
     """Row pitches larger than the row length (views into wider buffers); the last listed row holds
     the largest finite bf16 values: positions past the end of the list re-read that row and must
