@@ -47,7 +47,8 @@ def main():
 
     # A stored K-major (At[k][m]); sparsity in blocks of gm tokens x gk channels, i.e. At blocks of gk x gm
     vals = g.standard_normal((n, n)).astype(np.float32)
-    for gm, gk in ((32, 1), (32, 64), (128, 1)):
+    # (64, 32) is also the case of weights pruned in blocks of 32 k x 64 outputs, with the operand roles swapped
+    for gm, gk in ((32, 1), (32, 64), (128, 1), (64, 32)):
         for s in (0.0, 0.5, 0.9, 0.95, 0.99):
             keep = wl.iid_block_mask(n, n, gk, gm, s, seed=int(s * 100) + gm + gk)
             At = bf16(vals * keep)
@@ -62,10 +63,49 @@ def main():
             t = _time(step, a.reps)
             t_idx = _time(lambda: pit.pit_build_index(At, 1, 128, 0, out=ix, ws=ws), a.reps)
             torch.cuda.synchronize()
+            want = C.clone()
+            # the same step replayed from a HIP graph: the GPU's time without the host's launch calls
+            # (every replay is checked against the eager result)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()
+            torch.cuda.current_stream().wait_stream(side)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            ok = True
+            for _ in range(3):
+                C.fill_(-1.0)
+                graph.replay()
+                torch.cuda.synchronize()
+                ok = ok and bool(torch.equal(C, want))
+            t_graph = _time(graph.replay, a.reps)
             cover = int(ix.seg_ptr[-1].item()) / float((n // 128) * n)
             out["gemm"].append({"granularity_tokens_x_channels": [gm, gk], "sparsity": s, "cover_128x1": round(cover, 4),
                                 "step_ms": round(t * 1e3, 4), "index_ms": round(t_idx * 1e3, 4),
-                                "speedup_vs_dense": round(t_dense / t, 3)})
+                                "step_graph_ms": round(t_graph * 1e3, 4), "graph_matches_eager": ok,
+                                "speedup_vs_dense": round(t_dense / min(t, t_graph), 3)})
+
+    # A row-major [m][k], zeros in blocks of 1 token x 64 channels: PIT-axis m inside k-slabs of 64
+    # (GATHER_M, the slabs' partial products meet in C through fp32 atomics)
+    out["gemm_row_major_1x64"] = []
+    for s in (0.5, 0.9, 0.95, 0.99):
+        keep = wl.iid_block_mask(n, n, 1, 64, s, seed=int(s * 100) + 7)
+        A = bf16(vals * keep)
+        ix = pit.PitIndex.empty(n // 64, (n // 64) * n)
+        ws = torch.empty(pit.pit_build_index_workspace(n, n, 1, 64, 0), dtype=torch.uint8, device="cuda")
+        C = torch.empty((n, n), dtype=torch.float32, device="cuda")
+
+        def step_m():
+            pit.pit_build_index(A, 1, 64, 0, out=ix, ws=ws)
+            pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, A, B, ix, 64, n, n, n, out=C)
+
+        t = _time(step_m, a.reps)
+        torch.cuda.synchronize()
+        cover = int(ix.seg_ptr[-1].item()) / float((n // 64) * n)
+        out["gemm_row_major_1x64"].append({"sparsity": s, "cover_1x64": round(cover, 4), "step_ms": round(t * 1e3, 4),
+                                           "speedup_vs_dense": round(t_dense / t, 3)})
 
     # index build alone on byte masks (Section 5.4, "Sparsity detection"), 99 % sparsity
     for gr in (1, 16, 32):

@@ -656,14 +656,19 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     process(T, ra, rb);
   };
 
+  // With several tiles per workgroup the next tile's description and the list entries of its first
+  // two slabs are fetched ahead of the current tile's reduction, so that only the row loads remain
+  // between two tiles.
   uint4 ra0[8], rb0[8], ra1[8], rb1[8];
   PIT_LDS char* red = (PIT_LDS char*)s_red;
-  for (int lin = blockIdx.x; lin < total; lin += gridDim.x) {
-    const DirectTile T = tile_of(lin);
+  int lin = blockIdx.x;
+  DirectTile T = tile_of(lin);
+  int k0 = 0, k1 = 0;
+  if (T.n_w > 0) { k0 = load_list(T, 0); k1 = load_list(T, 1); }
+  for (;;) {
     if (T.n_w > 0) {
       // (the fences keep the list loads of slabs 2 and 3 ahead of the second slab's data loads: the
       // memory counter retires in order, so a list load issued last would make the loop wait for all)
-      int k0 = load_list(T, 0), k1 = load_list(T, 1);
       PIT_SCHED_FENCE();
       issue(T, k0, ra0, rb0); k0 = load_list(T, 2); PIT_SCHED_FENCE();
       issue(T, k1, ra1, rb1); k1 = load_list(T, 3); PIT_SCHED_FENCE();
@@ -681,6 +686,14 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
       process_last(T, t, ra0, rb0);
       PIT_MFMA_DRAIN();
     }
+    const int lin_next = lin + (int)gridDim.x;
+    const bool more = lin_next < total;
+    DirectTile Tn = T;
+    if (more) {
+      Tn = tile_of(lin_next);
+      if (Tn.n_w > 0) { k0 = load_list(Tn, 0); k1 = load_list(Tn, 1); }
+    }
+    PIT_SCHED_FENCE();
 
     // Reduction across the four waves, one quarter of the tile rows per round, double-buffered in
     // LDS: round P's partial sums are written before barrier P and read by wave P after it, while the
@@ -698,8 +711,10 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     if (wv != 3) red_send<3>(acc, red + RED_BUF_BYTES, wv, lane);
     __syncthreads();
     if (wv == 3) { red_recv<3>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 3>(acc, g, m_base, T.n0, lane); }
-    if (lin + (int)gridDim.x >= total) break;
+    if (!more) break;
     PIT_SCHED_FENCE();
+    lin = lin_next;
+    T = Tn;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
