@@ -21,6 +21,10 @@ What is defined here and where the paper fixes it
   results land at the token's original position.  Written as a per-token loop, no grouping.
 * ``sparse_attn``      -- attention restricted to a run-time mask (Section 5.1 "Longformer"):
   softmax over the allowed keys only.
+* ``relu_channel_major`` -- the activation that produces C2-like sparsity, handed over in the layout
+  Section 3.2 asks for when k is the PIT-axis (not contiguous along k), together with the index
+  Section 3.3's detection gives on that tensor.  It is the plain composition ReLU -> transpose ->
+  ``build_index``; the HIP side fuses the three.
 * ``cover_count`` / ``sparsity_after_cover`` -- CoverAlgo of Algorithm 1: how many micro-tiles of
   a given shape are needed to cover all non-zeros (Table 3, column "Sparsity Ratio After Cover").
 
@@ -185,6 +189,31 @@ def select_kernel(samples, candidates):
         if cost < best_cost:
             best, best_cost = i, cost
     return best, costs
+
+
+# ------------------------------------------------------------------------------------------------
+# the producer of activation sparsity (Sections 2.1 "ReLU", 3.2 layout, 3.3 detection)
+# ------------------------------------------------------------------------------------------------
+def relu(H: np.ndarray) -> np.ndarray:
+    """ReLU(x) = max(x, 0), element by element, in the storage type of H (uint16 = bf16 bits).
+
+    Reading (the paper does not discuss special values): both zeros and every negative value,
+    -Inf included, give +0; NaN is passed through unchanged (max with one NaN operand is not
+    ordered, and a NaN must stay visible); +Inf stays +Inf.
+    """
+    x = to_f64(H)
+    clamp = x <= 0                                   # False for NaN
+    zero = np.zeros((), dtype=H.dtype)
+    return np.where(clamp, zero, H)
+
+
+def relu_channel_major(H: np.ndarray, mt_tokens: int = 128):
+    """H is [tokens, channels].  Returns (Xt, seg_ptr, idx): Xt = ReLU(H) transposed to
+    [channels, tokens] and the index of Xt over micro-tiles of 1 channel x ``mt_tokens`` tokens with the
+    channel as PIT coordinate (one segment per block of ``mt_tokens`` tokens, listing its live channels)."""
+    Xt = np.ascontiguousarray(relu(H).T)
+    seg_ptr, idx, _ = build_index(Xt, 1, mt_tokens, 0)
+    return Xt, seg_ptr, idx
 
 
 # ------------------------------------------------------------------------------------------------
