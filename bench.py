@@ -203,6 +203,49 @@ def bench_relu_ffn_correlated(pit, wl, steps, warmup, pool=4):
     return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 10}
 
 
+def bench_relu_producer(pit, wl, steps, warmup, pool=4):
+    """The headline product fed from the pre-activation H[tokens][channels] (what the up-projection leaves
+    in HBM): ReLU, the change to the channel-major layout and the detection in one pass over H
+    (pit_relu_channel_major_index), against the same work done as an elementwise ReLU + transposed copy
+    followed by pit_build_index.  Zeros correlated across tokens as in relu_ffn_correlated_zeros."""
+    import numpy as np
+    import torch
+    M, K, N, MT = 2048, 8192, 2048, 128
+    Hs_np = [wl.relu_ffn_preactivation(M=M, K=K, call=c, channel_live_prob=0.25) for c in range(pool)]
+    Hs = [_to_dev(h) for h in Hs_np]
+    W = _to_dev(wl.relu_ffn(M=8, K=K, N=N, call=0).W)
+    relu_bits = [np.where((h & 0x8000) != 0, 0, h).astype(np.uint16) for h in Hs_np]      # finite data: sign test
+    eff = float(np.mean([2.0 * _count_nonzero_microtiles(np.ascontiguousarray(r.T), 32) * 32 * N for r in relu_bits]))
+    ix = pit.PitIndex.empty(M // MT, (M // MT) * K)
+    wsb = torch.empty(max(pit.pit_relu_channel_major_index_workspace(M, K), pit.pit_build_index_workspace(K, M, 1, MT, 0)),
+                      dtype=torch.uint8, device="cuda")
+    Xt = torch.empty((K, M), dtype=torch.bfloat16, device="cuda")
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+
+    def fused(i):
+        pit.pit_relu_channel_major_index(Hs[i % pool], out_xt=Xt, out=ix, ws=wsb)
+        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, MT, M, N, K, out=C)
+
+    def unfused(i):
+        Xt.copy_(torch.relu(Hs[i % pool]).t())
+        pit.pit_build_index(Xt, 1, MT, 0, out=ix, ws=wsb)
+        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, MT, M, N, K, out=C)
+
+    Cd = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+
+    def dense(i):
+        torch.matmul(torch.relu(Hs[i % pool]), W, out=Cd)
+
+    sec = _time_steps(fused, steps, warmup)
+    sec_unfused = _time_steps(unfused, steps, warmup)
+    sec_dense = _time_steps(dense, steps, warmup)
+    sec_producer = _time_steps(lambda i: pit.pit_relu_channel_major_index(Hs[i % pool], out_xt=Xt, out=ix, ws=wsb), steps, warmup)
+    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": sec_dense * 1e3,
+            "extra": {"unfused_ms_per_step": round(sec_unfused * 1e3, 4), "producer_ms": round(sec_producer * 1e3, 4),
+                      "producer_GB_per_s": round(2.0 * M * K * 2 / sec_producer / 1e9, 1),
+                      "dense_comparator": "torch.relu + hipBLASLt matmul on the token-major tensor"}}
+
+
 def bench_padded_linear(pit, wl, steps, warmup, pool=4):
     import numpy as np
     import torch
@@ -333,6 +376,7 @@ def _summary(r):
            "dense_ms": round(r["dense_ms"], 4), "speedup_vs_dense": round(r["dense_ms"] / (t * 1e3), 3)}
     if "hbm_floor_bytes" in r:
         out["frac_hbm_roofline"] = round(r["hbm_floor_bytes"] / t / 1e9 / HBM_PEAK_GBS, 4)
+    out.update(r.get("extra", {}))
     return out
 
 
@@ -394,6 +438,7 @@ def main():
         others = {}
         k, w_ = max(5, args.steps // 2), max(2, args.warmup // 2)
         for name, fn in [("relu_ffn_correlated_zeros", bench_relu_ffn_correlated),
+                         ("relu_ffn_from_preactivation", bench_relu_producer),
                          ("microtile_1x32_1024", bench_microtile), ("moe_switch_4096x64", bench_moe),
                          ("padded_batch_32x512", bench_padded_linear), ("sparse_attn_4096x12x64", bench_attn)]:
             if name.startswith("sparse_attn") and not hasattr(pit._lib, "pit_sparse_attn"):

@@ -107,6 +107,28 @@ size_t pit_build_route_index_workspace(int T, int E);
 int pit_build_route_index(const int32_t* d_expert_id, int T, int E, const pit_index* out,
                           int32_t* d_status, void* d_ws, size_t ws_bytes, pit_stream stream);
 
+/* Bytes of device workspace pit_relu_channel_major_index needs (0 on invalid arguments). */
+size_t pit_relu_channel_major_index_workspace(int tokens, int channels);
+
+/*
+ * The producer of activation sparsity, fused with the layout change and the detection: reads the
+ * pre-activation d_H [tokens x channels] (row-major, leading dimension ldh elements) once, writes
+ * d_Xt [channels x tokens] = ReLU(H)^T (leading dimension ldxt >= tokens) -- the layout paper
+ * Section 3.2 asks for when k is the PIT-axis of the product that follows -- and the index that
+ * pit_build_index(d_Xt, dt, channels, tokens, ldxt, 1, 128, 0, ...) would give on it (paper Section 3.3):
+ * one segment per block of 128 tokens listing, in ascending order, the channels with a non-zero
+ * activation in that block.  The tensor is not read a second time for the detection.
+ *   dt       PIT_BF16 or PIT_F16.  ReLU(x) = max(x, 0): both zeros and every negative value give +0,
+ *            NaN is passed through unchanged (and counts as non-zero), +Inf stays.
+ *   tokens   multiple of 128;  channels  multiple of 8;  ldh, ldxt multiples of 8; d_H, d_Xt 16-byte aligned.
+ *   out      out->nseg == tokens / 128, out->cap >= (tokens / 128) * channels, out->bits NULL.
+ *   d_ws     workspace of at least pit_relu_channel_major_index_workspace(...) bytes, 8-byte aligned.
+ * d_H and d_Xt must not overlap.  Errors as for pit_build_index.  tokens*channels == 0 is not an error.
+ */
+int pit_relu_channel_major_index(const void* d_H, int64_t ldh, int tokens, int channels, int dt,
+                                 void* d_Xt, int64_t ldxt, const pit_index* out,
+                                 void* d_ws, size_t ws_bytes, pit_stream stream);
+
 /* ---------------------------------------------------------------------------------------------
  * 1b. Micro-tile and kernel selection (paper Section 3.2, Algorithm 1)
  * ------------------------------------------------------------------------------------------- */

@@ -316,6 +316,76 @@ k_bitmap_tiles(const void* __restrict__ src, int64_t ld_bytes, int rows, int row
 }
 
 // ----------------------------------------------------------------------------------------------
+// Producer with the bitmap for free: Xt[k][m] = ReLU(H[m][k]) and, per block of 128 tokens, one
+// bit per channel "some activation is non-zero" (the bitmap of Xt at 1 x 128 micro-tiles, PIT-axis
+// = channels), in one pass over H.
+// A workgroup handles 128 tokens x 128 channels, wave w the channels 32 w .. 32 w + 31.  Lane l
+// loads 8 token rows x 16 B (tokens 8 (l % 16) + j, channels 8 (l / 16) ..+7 of the wave's 32), i.e.
+// an 8 x 8 block that it transposes in registers; its 8 stores then put 8 consecutive tokens of
+// one channel each, and 16 lanes cover the 256 contiguous bytes of a channel's 128 tokens.
+// Across the four waves a token row is read as 256 contiguous bytes.
+// ----------------------------------------------------------------------------------------------
+template <bool BF>
+__device__ __forceinline__ uint32_t relu_pair(uint32_t v) {
+  // per 16-bit half: negative and not NaN -> +0 (this includes -0 and -Inf); everything else unchanged
+  constexpr uint32_t INF = BF ? 0x7F80u : 0x7C00u;
+  const uint32_t lo = v & 0xFFFFu, hi = v >> 16;
+  const uint32_t rl = ((lo & 0x8000u) && (lo & 0x7FFFu) <= INF) ? 0u : lo;
+  const uint32_t rh = ((hi & 0x8000u) && (hi & 0x7FFFu) <= INF) ? 0u : hi;
+  return rl | (rh << 16);
+}
+
+template <bool BF>
+__global__ void __launch_bounds__(256)
+k_relu_transpose_bitmap(const void* __restrict__ H, int64_t ldh_bytes, int tokens, int channels,
+                        void* __restrict__ Xt, int64_t ldxt_bytes, int W, uint32_t* __restrict__ words32) {
+  const int wv = threadIdx.x >> 6, ln = lane_id();
+  const int tg = ln & 15, cg = ln >> 4;
+  const int t0 = blockIdx.y * 128 + 8 * tg;                       // first of this lane's 8 tokens
+  const int c0 = blockIdx.x * 128 + wv * 32 + 8 * cg;             // first of this lane's 8 channels
+  const bool ok = c0 < channels;                                  // channels % 8 == 0: all 8 or none
+  uint4 r[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    r[j] = make_uint4(0, 0, 0, 0);
+    if (ok) r[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(H) + (int64_t)(t0 + j) * ldh_bytes + (int64_t)c0 * 2);
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    r[j].x = relu_pair<BF>(r[j].x); r[j].y = relu_pair<BF>(r[j].y);
+    r[j].z = relu_pair<BF>(r[j].z); r[j].w = relu_pair<BF>(r[j].w);
+  }
+  // 8 x 8 transpose of 16-bit elements: o[c] = tokens t0 .. t0 + 7 of channel c0 + c
+  uint4 o[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t lo[4], hi[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const uint32_t a = i == 0 ? r[2 * jj].x : i == 1 ? r[2 * jj].y : i == 2 ? r[2 * jj].z : r[2 * jj].w;
+      const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
+      lo[jj] = __builtin_amdgcn_perm(b, a, 0x05040100u);
+      hi[jj] = __builtin_amdgcn_perm(b, a, 0x07060302u);
+    }
+    o[2 * i] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    o[2 * i + 1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+  }
+  uint32_t flags = 0;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    if (ok) *reinterpret_cast<uint4*>(reinterpret_cast<char*>(Xt) + (int64_t)(c0 + c) * ldxt_bytes + (int64_t)t0 * 2) = o[c];
+    flags |= (((o[c].x | o[c].y | o[c].z | o[c].w) & 0x7FFF7FFFu) != 0 ? 1u : 0u) << c;
+  }
+  // OR over the 16 lanes that share the channels, then the four channel groups side by side
+  flags |= __shfl_xor(flags, 1); flags |= __shfl_xor(flags, 2);
+  flags |= __shfl_xor(flags, 4); flags |= __shfl_xor(flags, 8);
+  const uint32_t word = (uint32_t)__shfl(flags, 0) | ((uint32_t)__shfl(flags, 16) << 8) |
+                        ((uint32_t)__shfl(flags, 32) << 16) | ((uint32_t)__shfl(flags, 48) << 24);
+  const int u = blockIdx.x * 4 + wv;                              // 32-bit unit inside the segment's bitmap row
+  if (ln == 0 && u < 2 * W) words32[((int64_t)blockIdx.y * W) * 2 + u] = word;
+}
+
+// ----------------------------------------------------------------------------------------------
 // pass 1 for routing decisions: segment e, bit t  <=>  expert_id[t] == e
 // ----------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
@@ -804,6 +874,41 @@ extern "C" int pit_build_index(const void* d_src, int dt, int rows, int cols, in
   const int rc = launch_bitmap(L, d_src, esize, rows, cols, ld, mt_rows, mt_cols, pit_dim, want_bits, words, occ, st);
   if (rc != PIT_OK) return rc;
   return launch_emit(L, words, cnt, occ, out, 0, nullptr, st);
+}
+
+extern "C" size_t pit_relu_channel_major_index_workspace(int tokens, int channels) {
+  if (tokens < 0 || channels < 0 || tokens % 128 || channels % 8) return 0;
+  return pit_build_index_workspace(channels, tokens, 1, 128, 0, 0);
+}
+
+extern "C" int pit_relu_channel_major_index(const void* d_H, int64_t ldh, int tokens, int channels, int dt,
+                                            void* d_Xt, int64_t ldxt, const pit_index* out,
+                                            void* d_ws, size_t ws_bytes, pit_stream stream) {
+  if (!out || !out->seg_ptr || out->bits || (dt != PIT_BF16 && dt != PIT_F16)) return PIT_EINVAL;
+  if (tokens < 0 || channels < 0 || tokens % 128 || channels % 8) return PIT_ESHAPE;
+  // the index of Xt[channels][tokens] at 1 x 128 micro-tiles with the channel as PIT coordinate
+  const Layout L = make_layout(channels, tokens, 1, 128, 0, 0);
+  if (out->nseg != L.nseg) return PIT_ECAPACITY;
+  if ((int64_t)out->cap < (int64_t)L.nseg * L.npit) return PIT_ECAPACITY;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (L.nseg == 0 || L.npit == 0) return launch_emit(L, nullptr, nullptr, nullptr, out, 0, nullptr, st);
+  if (ldh < channels || ldxt < tokens || ldh % 8 || ldxt % 8) return PIT_EINVAL;
+  if (!d_H || !d_Xt || !out->idx || !d_ws || !aligned(d_ws, 8) || !aligned(d_H, 16) || !aligned(d_Xt, 16)) return PIT_EINVAL;
+  if (ws_bytes < pit_relu_channel_major_index_workspace(tokens, channels)) return PIT_ECAPACITY;
+  if (tokens / 128 > 65535) return PIT_ESHAPE;
+
+  char* ws = reinterpret_cast<char*>(d_ws);
+  u64* words = reinterpret_cast<u64*>(ws);
+  int32_t* cnt = reinterpret_cast<int32_t*>(ws + L.words_bytes + L.occ_bytes);
+  dim3 grid((unsigned)ceil_div(channels, 128), (unsigned)(tokens / 128));
+  if (dt == PIT_BF16)
+    hipLaunchKernelGGL(k_relu_transpose_bitmap<true>, grid, dim3(256), 0, st, d_H, ldh * 2, tokens, channels, d_Xt,
+                       ldxt * 2, L.W, reinterpret_cast<uint32_t*>(words));
+  else
+    hipLaunchKernelGGL(k_relu_transpose_bitmap<false>, grid, dim3(256), 0, st, d_H, ldh * 2, tokens, channels, d_Xt,
+                       ldxt * 2, L.W, reinterpret_cast<uint32_t*>(words));
+  PIT_LAUNCH_CHECK();
+  return launch_emit(L, words, cnt, nullptr, out, 0, nullptr, st);
 }
 
 // The count does not depend on the PIT-axis; byte masks with column-shaped micro-tiles take the

@@ -25,6 +25,7 @@ _STATUS = {0: "PIT_OK", -1: "PIT_EINVAL", -2: "PIT_ESHAPE", -3: "PIT_ECAPACITY",
 
 EXPORTS = ["pit_last_hip_error", "pit_version", "pit_build_index_workspace", "pit_build_index",
            "pit_build_route_index_workspace", "pit_build_route_index",
+           "pit_relu_channel_major_index_workspace", "pit_relu_channel_major_index",
            "pit_cover_count_workspace", "pit_cover_count", "pit_select_kernel", "pit_sread_gemm",
            "pit_moe_workspace", "pit_moe_dispatch_gemm", "pit_sparse_attn_workspace", "pit_sparse_attn"]
 
@@ -46,6 +47,10 @@ _lib.pit_build_route_index_workspace.restype = c_sz
 _lib.pit_build_route_index_workspace.argtypes = [c_int, c_int]
 _lib.pit_build_route_index.restype = c_int
 _lib.pit_build_route_index.argtypes = [c_vp, c_int, c_int, _P, c_vp, c_vp, c_sz, c_vp]
+_lib.pit_relu_channel_major_index_workspace.restype = c_sz
+_lib.pit_relu_channel_major_index_workspace.argtypes = [c_int, c_int]
+_lib.pit_relu_channel_major_index.restype = c_int
+_lib.pit_relu_channel_major_index.argtypes = [c_vp, c_i64, c_int, c_int, c_int, c_vp, c_i64, _P, c_vp, c_sz, c_vp]
 
 
 class _CCandidate(ctypes.Structure):
@@ -169,6 +174,34 @@ def pit_build_route_index(expert_id: torch.Tensor, E: int, out: PitIndex | None 
     _check(_lib.pit_build_route_index(expert_id.data_ptr(), T, E, ctypes.byref(ci), _ptr(status), ws.data_ptr(),
                                       ws.numel(), _stream()), "pit_build_route_index")
     return out
+
+
+def pit_relu_channel_major_index_workspace(tokens, channels) -> int:
+    return _lib.pit_relu_channel_major_index_workspace(tokens, channels)
+
+
+def pit_relu_channel_major_index(H: torch.Tensor, out_xt: torch.Tensor | None = None, out: PitIndex | None = None,
+                                 ws: torch.Tensor | None = None):
+    """Xt = ReLU(H)^T ([channels, tokens]) and its index at 1 x 128 micro-tiles in one pass over H
+    ([tokens, channels], last dim contiguous).  Returns (Xt, index).  See include/pit.h."""
+    assert H.dim() == 2 and H.stride(1) == 1
+    tokens, channels = H.shape
+    if out_xt is None:
+        out_xt = torch.empty((channels, tokens), dtype=H.dtype, device=H.device)
+    if out is None:
+        if tokens % 128:
+            raise PitError(PIT_ESHAPE, "pit_relu_channel_major_index")
+        out = PitIndex.empty(tokens // 128, (tokens // 128) * channels, False, H.device)
+    if ws is None:
+        ws = torch.empty(max(pit_relu_channel_major_index_workspace(tokens, channels), 8), dtype=torch.uint8,
+                         device=H.device)
+    ci = out.c()
+    _check(_lib.pit_relu_channel_major_index(H.data_ptr(), H.stride(0) if tokens > 1 else max(channels, H.stride(0)),
+                                             tokens, channels, _dt(H), out_xt.data_ptr(),
+                                             out_xt.stride(0) if channels > 1 else max(tokens, out_xt.stride(0)),
+                                             ctypes.byref(ci), ws.data_ptr(), ws.numel(), _stream()),
+           "pit_relu_channel_major_index")
+    return out_xt, out
 
 
 def pit_cover_count_workspace(rows, cols, mt_rows, mt_cols) -> int:

@@ -111,6 +111,21 @@ def relu_ffn(M=2048, K=8192, N=2048, mean=-1.2, w_std=0.02, seed=None, call=0, i
     return ReluFfn(Xt=to_bf16_bits(X), W=to_bf16_bits(W), M=M, K=K, N=N)
 
 
+def relu_ffn_preactivation(M=2048, K=8192, mean=-1.2, seed=None, call=0, channel_live_prob: float | None = None) -> np.ndarray:
+    """The tensor one step before ``relu_ffn``'s X: H[M tokens, K channels] ~ N(mean, 1) as bf16 bits, token-major
+    (what an up-projection writes).  With ``channel_live_prob`` a channel is pushed below zero for a whole block of
+    128 tokens with probability 1 - channel_live_prob, so that ReLU(H) has the correlated zeros of ``relu_ffn``."""
+    g = rng_for(12, call, seed)
+    H = g.standard_normal((M, K), dtype=np.float32) + np.float32(mean)
+    if channel_live_prob is not None:
+        blk = 128
+        nb = (M + blk - 1) // blk
+        dead = g.random((nb, K)) >= channel_live_prob
+        dead = np.repeat(dead, blk, axis=0)[:M]
+        H = np.where(dead, -np.abs(H) - np.float32(0.5), H)
+    return to_bf16_bits(H)
+
+
 # --------------------------------------------------------------------------------------------
 # C3: top-1 mixture-of-experts FFN with skewed expert popularity
 # --------------------------------------------------------------------------------------------
