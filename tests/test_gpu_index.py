@@ -125,6 +125,22 @@ def test_vector_path_dense_and_strided(pit):
         _check(pit, np.ascontiguousarray(sub), mt[0], mt[1], 1, src_t=t)
 
 
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shapes_either_path(pit, seed):
+    """Seeded random shapes, micro-tiles, element sizes and densities: whichever bitmap and emit kernels the
+    library picks, the index must equal the oracle's."""
+    g = np.random.default_rng(9000 + seed)
+    dtype = [np.uint8, np.float16, np.float32][seed % 3]
+    mt_rows = int(g.choice([1, 1, 2, 3, 4, 5, 7, 8, 16, 17, 32, 33, 64, 65, 100]))
+    mt_cols = int(g.choice([1, 1, 2, 4, 8, 16, 32, 64, 128, 3, 5, 24]))
+    rows = mt_rows * int(g.integers(1, 10 if mt_rows > 8 else 300))
+    cols = mt_cols * int(g.integers(1, 12 if mt_cols > 8 else 700))
+    density = float(g.choice([0.0, 0.003, 0.05, 0.5, 1.0]))
+    src = ((g.random((rows, cols)) < density) * (1 + g.random((rows, cols)))).astype(dtype)
+    for pit_dim in (0, 1):
+        _check(pit, src, mt_rows, mt_cols, pit_dim)
+
+
 def test_strided_view_and_special_values(pit):
     g = np.random.default_rng(3)
     big = np.zeros((64, 256), dtype=np.float16)
