@@ -425,6 +425,7 @@ def main():
         "speedup_vs_dense": round(r["dense_ms"] / (sec * 1e3), 3),
         "dense_gemm_ms": round(r["dense_ms"], 4),
         "index_build_ms": round(r["index_ms"], 4), "gemm_ms": round(r["gemm_ms"], 4),
+        "index_build_GB_per_s": round(2.0 * 2048 * 8192 / (r["index_ms"] * 1e-3) / 1e9, 1),   # the tensor read once
         "gemm_kernel_ms": round(r["gemm_kernel_ms"], 4),
         "index_share_of_step": round(r["index_ms"] / (r["index_ms"] + r["gemm_ms"]), 4),
         "roofline": {"bound": "mfma", "kernel": "k_gather_k_direct (bf16)", "achieved": round(gemm_tflops, 2),

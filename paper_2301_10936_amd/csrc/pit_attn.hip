@@ -5,11 +5,13 @@
 //      every block of 32 queries, the ascending list of keys at least one of them attends to, and
 //      per listed key a 32-bit word saying which of the 32 queries do.
 //   2. One workgroup per (query block, head); its 4 wavefronts take the key list in chunks of 32
-//      keys, round-robin, each with its own running softmax state, merged at the end.
+//      keys, round-robin, each with its own running softmax state, merged at the end.  A wave's
+//      loop has no workgroup barrier and keeps the loads of its next chunk (and the list entries
+//      of the one after) in flight while it computes.
 //      Per chunk (everything is laid out so that lane % 32 == query):
-//        SRead   K rows of the listed keys go straight from global memory into MFMA A-operands
-//                (a K row is d-contiguous, which is what the operand wants); V rows are gathered
-//                into LDS as [key][d].
+//        SRead   the K and V rows of the listed keys are gathered into LDS as [key][d], each
+//                128-byte row fetched by 8 lanes at once; K operands are read back row-wise (a K
+//                row is d-contiguous, which is what the A operand wants).
 //        S^T   = K' . Q^T           4 x v_mfma_f32_32x32x16 (input type), fp32
 //        mask, running max / sum per query, P^T = exp2(S^T*c - m)        fp32, in registers
 //        O^T  += V'^T . P^T         4 x v_mfma_f32_32x32x16_f16; V'^T operands come from LDS with
@@ -77,10 +79,22 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
               const int32_t* __restrict__ seg_ptr, const int32_t* __restrict__ idx, const uint32_t* __restrict__ bits,
               void* __restrict__ O, int S, float scale_log2e) {
   __shared__ __attribute__((aligned(1024))) char s_v[4][V_TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char s_k[4][V_TILE_BYTES];
   __shared__ __attribute__((aligned(16))) uint32_t s_bits[4][KC];
   __shared__ float s_merge[3][64][34];
 
-  const int qb = blockIdx.x, head = blockIdx.y;
+  // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that an XCD
+  // works on a contiguous run of (head, query block) pairs, i.e. on the K and V of one or two heads
+  // (1 MiB per head at S = 4096), which then stay in its L2.
+  int qb, head;
+  {
+    const int nqb = gridDim.x, total = nqb * gridDim.y;
+    const int lin = blockIdx.x + nqb * blockIdx.y;
+    const int x = lin & 7, qq = total >> 3, rr = total & 7;
+    const int lp = x * qq + min(x, rr) + (lin >> 3);
+    head = lp / nqb;
+    qb = lp - head * nqb;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int h = lane >> 5, ql = lane & 31;
   const int list_begin = seg_ptr[qb];
@@ -102,44 +116,78 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
 
   const uint32_t v_lds = (uint32_t)(uintptr_t)(PIT_LDS char*)s_v[wv];
+  const uint32_t k_lds = (uint32_t)(uintptr_t)(PIT_LDS char*)s_k[wv];
 
-  for (int c0 = 0; c0 < nchunks; c0 += 4) {
-    const int c = c0 + wv;
-    const bool active = c < nchunks;          // uniform per wave
+  // This wave's chunks are wv, wv + 4, ...  The V tile and the mask words in LDS are private to the
+  // wave, so the loop needs no workgroup barrier, and it is software-pipelined: the list entries of
+  // chunk i + 2 and the K and V rows of chunk i + 1 are requested before chunk i is computed.
+  const int my_chunks = nchunks > wv ? (nchunks - wv + 3) >> 2 : 0;
+  auto load_key = [&](int i, int& key, uint32_t& bw) {
+    key = -1;
+    bw = 0u;
+    if (i < my_chunks) {
+      const int kk = (wv + 4 * i) * KC + ql;
+      if (kk < list_len) { key = idx[list_begin + kk]; bw = bits[list_begin + kk]; }
+    }
+  };
+  // SRead: the K and V rows of a chunk (32 x 128 B each) are fetched whole, 8 lanes x 16 B per row, so
+  // that every 128-byte line is requested once; both go through LDS on their way to the operands
+  auto load_kv = [&](int key, uint4 (&kf)[4], uint4 (&vr)[4]) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int x = it * 64 + lane;
+      const int krow = __shfl(key, x >> 3);
+      kf[it] = make_uint4(0, 0, 0, 0);
+      vr[it] = make_uint4(0, 0, 0, 0);
+      if (krow >= 0) {
+        kf[it] = *reinterpret_cast<const uint4*>(K + head_off + (int64_t)krow * HD + (x & 7) * 8);
+        vr[it] = *reinterpret_cast<const uint4*>(V + head_off + (int64_t)krow * HD + (x & 7) * 8);
+      }
+    }
+  };
+
+  int key_a, key_b;
+  uint32_t bw_a, bw_b;
+  uint4 kf0[4], vr0[4], kf1[4], vr1[4];
+  load_key(0, key_a, bw_a);
+  load_key(1, key_b, bw_b);
+  load_kv(key_a, kf0, vr0);
+  // one chunk: key_a / bw_a belong to chunk i (rows in kf, vr), key_b / bw_b to chunk i + 1
+  auto step = [&](int i, uint4 (&kf)[4], uint4 (&vr)[4], uint4 (&kf_n)[4], uint4 (&vr_n)[4]) {
+    int key_c;
+    uint32_t bw_c;
+    load_key(i + 2, key_c, bw_c);
+    load_kv(key_b, kf_n, vr_n);
+
+    if (h == 0) s_bits[wv][ql] = bw_a;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int x = it * 64 + lane;
+      uint4 v = vr[it];
+      if constexpr (BF) {
+        v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y);
+        v.z = bf16x2_to_f16x2(v.z); v.w = bf16x2_to_f16x2(v.w);
+      }
+      *(PIT_LDS u32x4_t*)(uintptr_t)(v_lds + v_off(x >> 3, x & 7)) = __builtin_bit_cast(u32x4_t, v);
+    }
+    // K tile [32 keys][8 chunks of 16 B], chunk index XOR-ed with (key >> 1) & 7: the straight writes
+    // and the operand reads (lane: key ql, chunk 2 ks + h) are both free of bank conflicts
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int x = it * 64 + lane;
+      const int r = x >> 3, c16 = x & 7;
+      *(PIT_LDS u32x4_t*)(uintptr_t)(k_lds + (uint32_t)(r * 128 + ((c16 ^ ((r >> 1) & 7)) << 4))) = __builtin_bit_cast(u32x4_t, kf[it]);
+    }
+    __builtin_amdgcn_wave_barrier();     // LDS writes above, LDS reads below: same wave, issued in order
     f32x16_t st;
 #pragma unroll
     for (int e = 0; e < 16; ++e) st[e] = 0.f;
-    if (active) {
-      const int kk = c * KC + ql;
-      const bool valid = kk < list_len;
-      const int key = valid ? idx[list_begin + kk] : -1;
-      if (h == 0) s_bits[wv][ql] = valid ? bits[list_begin + kk] : 0u;
-      // SRead K': rows straight into A-operands
-      uint4 kf[4];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        kf[ks] = make_uint4(0, 0, 0, 0);
-        if (valid) kf[ks] = *reinterpret_cast<const uint4*>(K + head_off + (int64_t)key * HD + ks * 16 + h * 8);
-      }
-      // SRead V': 32 rows x 128 B into LDS, 4 x 16 B per lane
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int x = it * 64 + lane;
-        const int r = x >> 3, c16 = x & 7;
-        const int krow = __shfl(key, r);
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (krow >= 0) v = *reinterpret_cast<const uint4*>(V + head_off + (int64_t)krow * HD + c16 * 8);
-        if constexpr (BF) {
-          v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y);
-          v.z = bf16x2_to_f16x2(v.z); v.w = bf16x2_to_f16x2(v.w);
-        }
-        *(PIT_LDS u32x4_t*)(uintptr_t)(v_lds + v_off(r, c16)) = __builtin_bit_cast(u32x4_t, v);
-      }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) st = mfma_in<BF>(kf[ks], qf[ks], st);
+    for (int ks = 0; ks < 4; ++ks) {
+      const u32x4_t ka = *(PIT_LDS u32x4_t*)(uintptr_t)(k_lds + (uint32_t)(ql * 128 + (((2 * ks + h) ^ ((ql >> 1) & 7)) << 4)));
+      st = mfma_in<BF>(__builtin_bit_cast(uint4, ka), qf[ks], st);
     }
-    __syncthreads();
-    if (active) {
+    {
       // st[j] = S^T[key 8*(j/4) + 4*h + j%4][query ql]
       float mx = -INFINITY;
 #pragma unroll
@@ -148,29 +196,33 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const bool on = (bw[e] >> ql) & 1u;
-          const float s = on ? st[g * 4 + e] * scale_log2e : -INFINITY;
-          st[g * 4 + e] = s;
-          mx = fmaxf(mx, s);
+          const float sc = on ? st[g * 4 + e] * scale_log2e : -INFINITY;
+          st[g * 4 + e] = sc;
+          mx = fmaxf(mx, sc);
         }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float m_new = fmaxf(m_run, mx);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = exp2f(m_run - m_safe);
+      // (the arguments are <= 0 or -inf: the bare hardware exp2 needs no range handling here)
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
       float psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float p = exp2f(st[e] - m_safe);
-        st[e] = p;
-        psum += p;
+        const float pe = __builtin_amdgcn_exp2f(st[e] - m_safe);
+        st[e] = pe;
+        psum += pe;
       }
       psum += __shfl_xor(psum, 32);
       l_run = l_run * alpha + psum;
+      // the running output is rescaled only when some query's maximum moved (alpha == 1 otherwise)
+      if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0ull) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+      }
       m_run = m_new;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
       // O^T += V'^T . P^T ; k-step t covers chunk keys 16t .. 16t+15 in the order the accumulator holds them
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -192,7 +244,13 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
         }
       }
     }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();     // the next chunk overwrites the tile just read
+    key_a = key_b; bw_a = bw_b;
+    key_b = key_c; bw_b = bw_c;
+  };
+  for (int i = 0; i < my_chunks; i += 2) {      // the two row buffers alternate
+    step(i, kf0, vr0, kf1, vr1);
+    if (i + 1 < my_chunks) step(i + 1, kf1, vr1, kf0, vr0);
   }
 
   // merge the 4 wavefronts' partial (m, l, O) per lane; wave 0 finishes
