@@ -110,41 +110,56 @@ k_bitmap_rows(const void* __restrict__ src, int64_t ld_bytes, int rows, int row_
 }
 
 // ----------------------------------------------------------------------------------------------
-// pass 1, fast path B: PIT-axis = columns, byte mask, micro-tile = mt_rows x 1.
-// A wave covers one segment (mt_rows rows) x 1024 columns; a lane owns 16 columns and keeps one
-// occupancy word per column (bit r = row r of the micro-tile is non-zero).
+// pass 1, fast path B: PIT-axis = columns, byte mask, micro-tile = mt_rows x 1, with the element
+// occupancy of every micro-tile.  A workgroup covers one segment (mt_rows rows) x 1024 columns; a
+// lane owns 16 columns and keeps one occupancy word per column (bit r = row r of the micro-tile is
+// non-zero).  The four waves split the rows (wave w takes rows w, w + 4, ...), so that a 32-row
+// micro-tile is one batch of 8 row loads per wave; their partial words are OR-ed through LDS.
 // ----------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 k_bitmap_cols_u8(const uint8_t* __restrict__ src, int64_t ld, int mt_rows, int cols, int nseg, int npit, int W,
                  u64* __restrict__ words, uint32_t* __restrict__ occ) {
+  __shared__ uint4 part[3][4][64];
   const int chunks = (W * 64 + 1023) / 1024;
-  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (wave >= (int64_t)nseg * chunks) return;
-  const int s = (int)(wave / chunks), ch = (int)(wave % chunks);
-  const int c0 = ch * 1024 + lane_id() * 16;
-  if (c0 >= W * 64) return;
+  const int s = blockIdx.x / chunks, ch = blockIdx.x % chunks;
+  const int wv = threadIdx.x >> 6, ln = lane_id();
+  const int c0 = ch * 1024 + ln * 16;
   uint32_t o[16];
 #pragma unroll
   for (int j = 0; j < 16; ++j) o[j] = 0;
   if (c0 < cols) {
     const uint8_t* p = src + (int64_t)s * mt_rows * ld + c0;
-    for (int r0 = 0; r0 < mt_rows; r0 += 8) {
+    for (int r0 = wv; r0 < mt_rows; r0 += 32) {
       uint4 v[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         v[i] = make_uint4(0, 0, 0, 0);
-        if (r0 + i < mt_rows) v[i] = *reinterpret_cast<const uint4*>(p + (int64_t)(r0 + i) * ld);
+        if (r0 + 4 * i < mt_rows) v[i] = *reinterpret_cast<const uint4*>(p + (int64_t)(r0 + 4 * i) * ld);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
+        const int r = r0 + 4 * i;
         const uint32_t d[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-        const uint32_t rb = (r0 + i) < 32 ? (1u << ((r0 + i) & 31)) : 0x80000000u;  // rows >= 32 only feed the flag
+        const uint32_t rb = r < 32 ? (1u << (r & 31)) : 0x80000000u;  // rows >= 32 only feed the flag
 #pragma unroll
         for (int j = 0; j < 16; ++j)
           if ((d[j >> 2] >> ((j & 3) * 8)) & 0xFFu) o[j] |= rb;
       }
     }
   }
+  if (wv > 0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) part[wv - 1][q][ln] = make_uint4(o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]);
+  }
+  __syncthreads();
+  if (wv != 0 || c0 >= W * 64) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint4 t = part[w][q][ln];
+      o[4 * q] |= t.x; o[4 * q + 1] |= t.y; o[4 * q + 2] |= t.z; o[4 * q + 3] |= t.w;
+    }
   uint32_t flags = 0;
 #pragma unroll
   for (int j = 0; j < 16; ++j) flags |= (o[j] != 0 ? 1u : 0u) << j;
@@ -827,8 +842,7 @@ static int launch_bitmap(const Layout& L, const void* d_src, int esize, int rows
     return launch_bitmap_tiles(L, d_src, esize, rows, (int)row_bytes, ld * esize, mt_rows, (int)mt_bytes, pit_dim, words, st);
   } else if (pit_dim == 1 && mt_cols == 1 && esize == 1 && vec_ok && cols % 16 == 0) {
     const int chunks = (L.W * 64 + 1023) / 1024;
-    const int64_t waves = (int64_t)L.nseg * chunks;
-    hipLaunchKernelGGL(k_bitmap_cols_u8, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st,
+    hipLaunchKernelGGL(k_bitmap_cols_u8, dim3((unsigned)((int64_t)L.nseg * chunks)), dim3(256), 0, st,
                        reinterpret_cast<const uint8_t*>(d_src), ld, mt_rows, cols, L.nseg, L.npit, L.W, words, occ);
   } else {
     const int64_t waves = (int64_t)L.nseg * L.W;
