@@ -502,6 +502,26 @@ __device__ __forceinline__ void red_recv(f32x4_t (&acc)[8][8], PIT_LDS char* buf
     PIT_SCHED_FENCE();
   }
 }
+// Two-wave workgroups: half H of the tile = the row groups ja in {4H .. 4H + 3}.
+constexpr int RED_HALF_BYTES = 32 * 64 * 16;
+template <int H>
+__device__ __forceinline__ void red_send_half(const f32x4_t (&acc)[8][8], PIT_LDS char* slot) {
+#pragma unroll
+  for (int i = 0; i < 32; ++i) *(PIT_LDS f32x4_t*)(slot + i * 1024) = acc[4 * H + (i >> 3)][i & 7];
+}
+template <int H>
+__device__ __forceinline__ void red_recv_half(f32x4_t (&acc)[8][8], PIT_LDS char* slot) {
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    f32x4_t part[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) part[i] = *(PIT_LDS f32x4_t*)(slot + (a * 16 + i) * 1024);
+    PIT_SCHED_FENCE();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[4 * H + 2 * a + (i >> 3)][i & 7] += part[i];
+    PIT_SCHED_FENCE();
+  }
+}
 // Wave P stores its quarter of the tile: rows 32 * (lane / 16) + 8 e + ja; a lane holds 8
 // consecutive columns of such a row (one per jb), so 16 lanes write 512 (fp32) or 256 contiguous bytes.
 template <bool BF, int CT, int P>
@@ -540,11 +560,15 @@ struct DirectTile {
   uint32_t a_col, b_col;           // this lane's byte offsets into a row of At and of B
 };
 
-template <bool BF, int CT>
-__global__ void __launch_bounds__(256)
+// NW = waves per workgroup that split the k-list: 4 (one workgroup fills a compute unit) or 2 (two
+// workgroups, i.e. two tiles, share a compute unit at the same register cost, and the set-up, drain,
+// reduction and stores of one tile run under the MFMA loop of the other; used when there are at
+// least two tiles per compute unit).
+template <bool BF, int CT, int NW>
+__global__ void __launch_bounds__(64 * NW)
 k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
   constexpr int SK = 32;   // list entries per slab = k extent of one MFMA
-  __shared__ __attribute__((aligned(16))) char s_red[2 * RED_BUF_BYTES];
+  __shared__ __attribute__((aligned(16))) char s_red[NW == 4 ? 2 * RED_BUF_BYTES : 2 * RED_HALF_BYTES];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -571,7 +595,7 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     const int list_begin = g.seg_ptr[t.seg];
     t.list_len = g.seg_ptr[t.seg + 1] - list_begin;
     const int nslab = (t.list_len + SK - 1) / SK;
-    t.n_w = nslab > wv ? (nslab - wv + 3) >> 2 : 0;   // this wave's slabs: wv, wv + 4, ...
+    t.n_w = nslab > wv ? (nslab - wv + NW - 1) / NW : 0;   // this wave's slabs: wv, wv + NW, ...
     t.list = uniform_ptr(g.idx + list_begin);
     t.a_col = (uint32_t)(t.seg * TM + 8 * q) * 2u;
     t.b_col = (uint32_t)(t.n0 + 8 * q) * 2u;
@@ -580,7 +604,7 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
 
   // lane l of a slab's list load holds entry (l % 32) of the slab
   auto load_list = [&](const DirectTile& T, int t) -> int {
-    const int pos = min(SK * (wv + 4 * t) + (lane & 31), T.list_len - 1);
+    const int pos = min(SK * (wv + NW * t) + (lane & 31), T.list_len - 1);
     typedef const int __attribute__((address_space(1))) * gint_t;
     return *(gint_t)(uintptr_t)(reinterpret_cast<uintptr_t>(T.list) + (uint32_t)pos * 4u);
   };
@@ -649,7 +673,7 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
   auto process_issue = [&](const DirectTile& T, uint4 (&ra)[8], uint4 (&rb)[8], int kraw) { process_impl(T, ra, rb, kraw, std::true_type{}); };
   // local slab t with the rows of positions past the end of the list zeroed
   auto process_last = [&](const DirectTile& T, int t, uint4 (&ra)[8], uint4 (&rb)[8]) {
-    const int p0 = SK * (wv + 4 * t) + 8 * kb;
+    const int p0 = SK * (wv + NW * t) + 8 * kb;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       if (p0 + i >= T.list_len) { ra[i] = make_uint4(0, 0, 0, 0); rb[i] = make_uint4(0, 0, 0, 0); }
@@ -695,22 +719,39 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     }
     PIT_SCHED_FENCE();
 
-    // Reduction across the four waves, one quarter of the tile rows per round, double-buffered in
-    // LDS: round P's partial sums are written before barrier P and read by wave P after it, while the
-    // other waves already write round P + 1 into the other buffer.
     const int m_base = T.seg * TM;
-    if (wv != 0) red_send<0>(acc, red, wv, lane);
-    __syncthreads();
-    if (wv == 0) { red_recv<0>(acc, red, lane); red_store<BF, CT, 0>(acc, g, m_base, T.n0, lane); }
-    if (wv != 1) red_send<1>(acc, red + RED_BUF_BYTES, wv, lane);
-    __syncthreads();
-    if (wv == 1) { red_recv<1>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 1>(acc, g, m_base, T.n0, lane); }
-    if (wv != 2) red_send<2>(acc, red, wv, lane);
-    __syncthreads();
-    if (wv == 2) { red_recv<2>(acc, red, lane); red_store<BF, CT, 2>(acc, g, m_base, T.n0, lane); }
-    if (wv != 3) red_send<3>(acc, red + RED_BUF_BYTES, wv, lane);
-    __syncthreads();
-    if (wv == 3) { red_recv<3>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 3>(acc, g, m_base, T.n0, lane); }
+    if constexpr (NW == 4) {
+      // Reduction across the four waves, one quarter of the tile rows per round, double-buffered in
+      // LDS: round P's partial sums are written before barrier P and read by wave P after it, while the
+      // other waves already write round P + 1 into the other buffer.
+      if (wv != 0) red_send<0>(acc, red, wv, lane);
+      __syncthreads();
+      if (wv == 0) { red_recv<0>(acc, red, lane); red_store<BF, CT, 0>(acc, g, m_base, T.n0, lane); }
+      if (wv != 1) red_send<1>(acc, red + RED_BUF_BYTES, wv, lane);
+      __syncthreads();
+      if (wv == 1) { red_recv<1>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 1>(acc, g, m_base, T.n0, lane); }
+      if (wv != 2) red_send<2>(acc, red, wv, lane);
+      __syncthreads();
+      if (wv == 2) { red_recv<2>(acc, red, lane); red_store<BF, CT, 2>(acc, g, m_base, T.n0, lane); }
+      if (wv != 3) red_send<3>(acc, red + RED_BUF_BYTES, wv, lane);
+      __syncthreads();
+      if (wv == 3) { red_recv<3>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 3>(acc, g, m_base, T.n0, lane); }
+    } else {
+      // The two waves trade the halves of their partial tiles that the other one owns (wave 0: the
+      // row groups ja < 4).  The first barrier keeps a wave from overwriting what the other still
+      // reads for the previous tile.
+      __syncthreads();
+      if (wv == 0) red_send_half<1>(acc, red + lane * 16);
+      else         red_send_half<0>(acc, red + RED_HALF_BYTES + lane * 16);
+      __syncthreads();
+      if (wv == 0) {
+        red_recv_half<0>(acc, red + RED_HALF_BYTES + lane * 16);
+        red_store<BF, CT, 0>(acc, g, m_base, T.n0, lane); red_store<BF, CT, 1>(acc, g, m_base, T.n0, lane);
+      } else {
+        red_recv_half<1>(acc, red + lane * 16);
+        red_store<BF, CT, 2>(acc, g, m_base, T.n0, lane); red_store<BF, CT, 3>(acc, g, m_base, T.n0, lane);
+      }
+    }
     if (!more) break;
     PIT_SCHED_FENCE();
     lin = lin_next;
@@ -773,8 +814,12 @@ static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
     static_assert(EPI == EPI_STORE, "GATHER_K has the plain store epilogue only");
     // one workgroup fits on a compute unit: with more tiles than compute units the workgroups loop
     const int total = (int)(grid.x * grid.y), cus = compute_units();
-    const unsigned wgs = (unsigned)(total <= cus ? total : cus);
-    hipLaunchKernelGGL((k_gather_k_direct<BF, CT>), dim3(wgs), dim3(256), 0, st, g, (int)grid.y);
+    if (total >= 2 * cus) {      // two workgroups of two waves per compute unit
+      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2>), dim3((unsigned)(2 * cus)), dim3(128), 0, st, g, (int)grid.y);
+    } else {
+      const unsigned wgs = (unsigned)(total <= cus ? total : cus);
+      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 4>), dim3(wgs), dim3(256), 0, st, g, (int)grid.y);
+    }
     PIT_LAUNCH_CHECK();
     return PIT_OK;
   } else {
