@@ -4,7 +4,8 @@
  * The library implements the run-time half of permutation-invariant transformation (PIT):
  *   1. online sparsity detection  -- find the non-zero micro-tiles of a tensor that stays in its
  *      ordinary dense storage and list their coordinates along the PIT-axis      (paper Section 3.3)
- *   2. SRead   -- gather the listed micro-tiles from global memory into dense tiles in LDS
+ *   2. SRead   -- gather the listed micro-tiles from global memory into dense operand tiles on chip
+ *      (LDS, or straight into registers)
  *   3. dense tile compute on the matrix cores (bf16/fp16 inputs, fp32 accumulation)
  *   4. SWrite  -- write the dense result tile back to the original coordinates
  *                                                    (paper Section 3.1, sparse kernel template)
