@@ -78,10 +78,11 @@ __global__ void __launch_bounds__(256)
 k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
               const int32_t* __restrict__ seg_ptr, const int32_t* __restrict__ idx, const uint32_t* __restrict__ bits,
               void* __restrict__ O, int S, float scale_log2e) {
-  __shared__ __attribute__((aligned(1024))) char s_v[4][V_TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char s_k[4][V_TILE_BYTES];
+  // per wave: its V tile and its K tile (8 KiB, private); after the loop the same 8 KiB carry the
+  // wave's partial output to wave 0 (32 floats per lane, laid out [value][lane])
+  __shared__ __attribute__((aligned(1024))) char s_kv[4][2 * V_TILE_BYTES];
   __shared__ __attribute__((aligned(16))) uint32_t s_bits[4][KC];
-  __shared__ float s_merge[3][64][34];
+  __shared__ float s_ml[3][2][64];
 
   // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that an XCD
   // works on a contiguous run of (head, query block) pairs, i.e. on the K and V of one or two heads
@@ -115,8 +116,8 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
 
-  const uint32_t v_lds = (uint32_t)(uintptr_t)(PIT_LDS char*)s_v[wv];
-  const uint32_t k_lds = (uint32_t)(uintptr_t)(PIT_LDS char*)s_k[wv];
+  const uint32_t v_lds = (uint32_t)(uintptr_t)(PIT_LDS char*)s_kv[wv];
+  const uint32_t k_lds = v_lds + V_TILE_BYTES;
 
   // This wave's chunks are wv, wv + 4, ...  The V tile and the mask words in LDS are private to the
   // wave, so the loop needs no workgroup barrier, and it is software-pipelined: the list entries of
@@ -255,19 +256,19 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
 
   // merge the 4 wavefronts' partial (m, l, O) per lane; wave 0 finishes
   if (wv > 0) {
-    float* dst = s_merge[wv - 1][lane];
-    dst[0] = m_run;
-    dst[1] = l_run;
+    float* dst = reinterpret_cast<float*>(s_kv[wv]);      // this wave's own tiles: nobody else reads them
+    s_ml[wv - 1][0][lane] = m_run;
+    s_ml[wv - 1][1][lane] = l_run;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) dst[2 + t * 16 + e] = o[t][e];
+      for (int e = 0; e < 16; ++e) dst[(t * 16 + e) * 64 + lane] = o[t][e];
   }
   __syncthreads();
   if (wv != 0) return;
   float m_all = m_run;
 #pragma unroll
-  for (int w = 0; w < 3; ++w) m_all = fmaxf(m_all, s_merge[w][lane][0]);
+  for (int w = 0; w < 3; ++w) m_all = fmaxf(m_all, s_ml[w][0][lane]);
   const float m_safe = m_all == -INFINITY ? 0.f : m_all;
   float a = exp2f(m_run - m_safe);
   float l_all = l_run * a;
@@ -277,13 +278,13 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
     for (int e = 0; e < 16; ++e) o[t][e] *= a;
 #pragma unroll
   for (int w = 0; w < 3; ++w) {
-    const float* src = s_merge[w][lane];
-    a = exp2f(src[0] - m_safe);
-    l_all += src[1] * a;
+    const float* src = reinterpret_cast<const float*>(s_kv[w + 1]);
+    a = exp2f(s_ml[w][0][lane] - m_safe);
+    l_all += s_ml[w][1][lane] * a;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) o[t][e] += src[2 + t * 16 + e] * a;
+      for (int e = 0; e < 16; ++e) o[t][e] += src[(t * 16 + e) * 64 + lane] * a;
   }
   const float inv = l_all > 0.f ? 1.f / l_all : 0.f;
   // o[dt][4*g + e] = O[query ql][d = 32*dt + 8*g + 4*h + e]
