@@ -88,7 +88,7 @@ def main():
                                 "speedup_vs_dense": round(t_dense / min(t, t_graph), 3)})
 
     # A row-major [m][k], zeros in blocks of 1 token x 64 channels: PIT-axis m inside k-slabs of 64
-    # (GATHER_M, the slabs' partial products meet in C through fp32 atomics)
+    # (GATHER_M, the slabs' partial products are added in strips of C held in LDS)
     out["gemm_row_major_1x64"] = []
     for s in (0.5, 0.9, 0.95, 0.99):
         keep = wl.iid_block_mask(n, n, 1, 64, s, seed=int(s * 100) + 7)

@@ -185,8 +185,12 @@ typedef enum pit_gemm_mode {
    * micro-tile in that slab is non-zero.  For every segment: C[rows, :] += A[rows, slab] . B[slab, :].
    * nseg == 1 (mt == K, whole-row micro-tiles: padded batches) stores each listed row once;
    * rows not listed are zero-filled if zero_uncovered != 0, else left untouched.
-   * nseg  > 1 accumulates with fp32 atomics into C, which the library zero-fills first
-   * (c_dt must be PIT_F32; summation order, hence the last bits, may vary from run to run).
+   * nseg  > 1 (micro-tiles along k): every element of C is written, rows that no slab lists as
+   * zeros, so C needs no clearing and zero_uncovered is ignored.  c_dt must be PIT_F32.  The slabs'
+   * partial products are added in an order that depends on the shape only (no atomics): the result
+   * is the same bits from run to run.  The lists must be ascending, as pit_build_index builds them.
+   * Limits of this case (else PIT_ESHAPE): lda, ldb < 2^23 elements, M, K < 2^24, M*lda and K*ldb
+   * < 2^31 elements, M <= 32 * 65535.
    */
   PIT_GEMM_GATHER_M = 0,
   /*

@@ -23,9 +23,9 @@
 // there is a single wavefront per SIMD.
 //
 // SWrite.  The GATHER_M epilogue stores accumulator rows to the row numbers held in LDS (compact or
-// from the index), optionally through fp32 atomics (several k-slabs accumulate into one C), a GELU
-// + round to the input type (first MoE matmul) or a per-row gate (second MoE matmul).  GATHER_K
-// writes the rows of its m-tile in place.
+// from the index), optionally with a GELU + round to the input type (first MoE matmul) or a per-row
+// gate (second MoE matmul).  GATHER_K writes the rows of its m-tile in place.  Several k-slabs per
+// row (micro-tiles along k) have a kernel of their own, k_slab_strip, which keeps C in LDS.
 #include "pit_gemm.hpp"
 #include <type_traits>
 
@@ -422,9 +422,7 @@ k_gather_m(const GemmArgs g) {
         float v = acc[i][j][e];
         if constexpr (EPI == EPI_GELU) v = gelu_erf_fast(v);
         if constexpr (EPI == EPI_STORE) v *= scale;
-        if constexpr (EPI == EPI_ATOMIC) {
-          atomicAdd(reinterpret_cast<float*>(g.C) + crow * g.ldc + col, v);
-        } else if constexpr (CT == 0) {
+        if constexpr (CT == 0) {
           reinterpret_cast<float*>(g.C)[crow * g.ldc + col] = v;
         } else {
           reinterpret_cast<uint16_t*>(g.C)[crow * g.ldc + col] = f32_to_in<BF>(v);
@@ -763,6 +761,275 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// GATHER_M with micro-tiles along k (several k-slabs per row: 1 x mt micro-tiles of a row-major A).
+//
+// The rows listed for slab s differ from those of slab s', so the partial products of the slabs
+// have to meet in C.  Here C stays put: a workgroup owns a strip of R rows x W columns of C
+// (R x W = 4096: 64 x 64, or 32 x 128) and walks ALL slabs; per slab it gathers the strip's listed
+// rows (SRead along m inside the strip, in blocks of 16 rows), multiplies them with the slab's rows
+// of B on v_mfma_f32_16x16x32, and adds the result to the strip held in LDS.  The four waves take
+// the slabs round-robin, each with a strip of its own (no atomics, no races); at the end the four
+// strips are added in a fixed order and the whole strip is stored, rows that nothing touched as
+// zeros.  So the result does not depend on the order in which anything ran, and C needs no clearing
+// beforehand.  B is read once per strip of rows, so its traffic falls with R; A is read once per
+// strip of columns.
+//   rows of a slab inside the strip: the slab's list is ascending, so they are one contiguous run
+//   of it; a 64-ary search by the wave finds where the run starts, two 64-entry loads hold it.
+//   A operand: 16 bytes (8 k) of a listed row per lane -- already the operand layout.
+//   B operand: 8 k-rows x CW columns (CW = W / 16) per lane, transposed inside the lane.
+//   strip in LDS: a lane moves the CW columns it holds of a row as 16-byte vectors and the 16
+//   lanes of a row lie side by side; a spare row swallows the results of unused block rows.
+// ------------------------------------------------------------------------------------------------
+constexpr int SS_BATCH = 8;                          // slabs per wave whose row lookups are in flight together
+static_assert(SS_BATCH == 8, "the lane layout of the list-bounds load assumes 8");
+template <int CW> struct StripShape {
+  static_assert(CW == 4 || CW == 8, "columns per lane");
+  static constexpr int W = 16 * CW;                  // columns of C per workgroup
+  static constexpr int R = 4096 / W;                 // rows of C per workgroup (at most 64: one lane per listed row)
+  static constexpr int FLOATS = (R + 1) * W;         // one wave's strip, with the spare row
+};
+
+// CW 16-bit columns of one k-row, as loaded
+template <int CW> struct BRow { uint32_t d[CW / 2]; };
+template <int CW>
+__device__ __forceinline__ BRow<CW> load_brow(const char* base, uint32_t byte_off) {
+  BRow<CW> r;
+  if constexpr (CW == 8) {
+    const uint4 v = load16(base, byte_off);
+    r.d[0] = v.x; r.d[1] = v.y; r.d[2] = v.z; r.d[3] = v.w;
+  } else {
+    typedef const u32x2_t __attribute__((address_space(1))) * gptr_t;
+    const u32x2_t v = *(gptr_t)(uintptr_t)(reinterpret_cast<uintptr_t>(base) + byte_off);
+    r.d[0] = v[0]; r.d[1] = v[1];
+  }
+  return r;
+}
+// 8 consecutive k of column x out of 8 k-rows (4 v_perm_b32)
+template <int CW>
+__device__ __forceinline__ uint4 bcolumn(const BRow<CW> (&r)[8], int x) {
+  const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+  uint32_t d[4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) d[jj] = __builtin_amdgcn_perm(r[2 * jj + 1].d[x >> 1], r[2 * jj].d[x >> 1], sel);
+  return make_uint4(d[0], d[1], d[2], d[3]);
+}
+
+template <bool BF>
+__device__ __forceinline__ f32x4_t mfma16(const uint4& a, const uint4& b, const f32x4_t& c) {
+  if constexpr (BF)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+template <bool BF, int CW>
+__global__ void __launch_bounds__(256, 2)
+k_slab_strip(const GemmArgs g) {
+  using SH = StripShape<CW>;
+  constexpr int SS_RM = SH::R;
+  __shared__ __attribute__((aligned(16))) float s_c[4][SH::FLOATS];
+  __shared__ __attribute__((aligned(16))) int s_rows[4][SS_BATCH][64];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q = lane & 15, kb = lane >> 4;
+  const int n0 = blockIdx.x * SH::W;
+  const int r0 = blockIdx.y * SS_RM;
+  float* strip = s_c[wv];
+  for (int i = lane * 4; i < SH::FLOATS; i += 256) *reinterpret_cast<f32x4_t*>(strip + i) = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const char* a_src = uniform_ptr(g.A);
+  const char* b_src = uniform_ptr(g.B);
+  const uint32_t pitch_a = (uint32_t)(g.lda * 2), pitch_b = (uint32_t)(g.ldb * 2);
+  const uint32_t b_lane = __umul24((uint32_t)(8 * kb), pitch_b) + (uint32_t)(n0 + CW * q) * 2u;
+  const int ksteps = g.slab / 32;                   // items per block of a slab
+  const int nsl = g.nseg > wv ? (g.nseg - wv + 3) >> 2 : 0;   // this wave's slabs: wv, wv + 4, ...
+
+  for (int j0 = 0; j0 < nsl; j0 += SS_BATCH) {
+    // ---- which rows of the strip does each slab of the batch list?  rowsel[j]: lane i < cnt[j]
+    //      holds the i-th of them (ascending)
+    int rowsel[SS_BATCH], cnt[SS_BATCH];
+    int lo[SS_BATCH], hi[SS_BATCH], end[SS_BATCH];
+    // one vector load brings the batch's list bounds: lane j the start of slab j's list, lane 8 + j its end
+    // (slabs past the last: slab 0 stands in, so that nothing branches)
+    const int pv = g.seg_ptr[(j0 + (lane & 7) < nsl ? wv + 4 * (j0 + (lane & 7)) : 0) + ((lane >> 3) & 1)];
+#pragma unroll
+    for (int j = 0; j < SS_BATCH; ++j) {
+      const bool valid = j0 + j < nsl;                         // slabs past the end: empty
+      lo[j] = valid ? __builtin_amdgcn_readlane(pv, j) : 0;
+      end[j] = valid ? __builtin_amdgcn_readlane(pv, SS_BATCH + j) : 0;
+      hi[j] = end[j];
+    }
+    // 64-ary search for p* = the first position whose entry is >= r0.  Invariant: lo <= p* <= hi, every
+    // entry before lo is below r0, the entry at hi (if hi < end) is not.  All slabs of the batch advance
+    // together, one round trip to memory per round.
+    for (;;) {
+      bool any_wide = false;
+#pragma unroll
+      for (int j = 0; j < SS_BATCH; ++j) any_wide |= hi[j] - lo[j] > 64;
+      if (!any_wide) break;
+      // every slab of the batch takes the round (it leaves a narrow range correct and no wider), so the code
+      // is free of branches and the eight loads are in flight together; entry 0 exists because some list is wide
+      int smp[SS_BATCH], step[SS_BATCH];
+#pragma unroll
+      for (int j = 0; j < SS_BATCH; ++j) {
+        step[j] = (hi[j] - lo[j] + 63) / 64;
+        const int pos = lo[j] + lane * step[j];
+        const int v = g.idx[max(min(pos, hi[j] - 1), 0)];
+        smp[j] = pos < hi[j] ? v : 0x7fffffff;
+      }
+#pragma unroll
+      for (int j = 0; j < SS_BATCH; ++j) {
+        const int c = __popcll(__ballot(smp[j] < r0));        // samples below the strip: a prefix
+        const int hi_new = (c < 64 && lo[j] + c * step[j] < hi[j]) ? lo[j] + c * step[j] : hi[j];
+        hi[j] = c == 0 ? lo[j] : hi_new;
+        lo[j] = c == 0 ? lo[j] : lo[j] + (c - 1) * step[j] + 1;
+      }
+    }
+    // the run of entries inside [r0, r0 + R) starts at most 64 positions after lo and is at most R <= 64 long
+    int e0[SS_BATCH], e1[SS_BATCH];
+#pragma unroll
+    for (int j = 0; j < SS_BATCH; ++j) {
+      const int p0 = lo[j] + lane, p1 = lo[j] + 64 + lane;
+      e0[j] = p0 < end[j] ? g.idx[p0] : 0x7fffffff;
+      e1[j] = p1 < end[j] ? g.idx[p1] : 0x7fffffff;
+    }
+#pragma unroll
+    for (int j = 0; j < SS_BATCH; ++j) {
+      const bool in0 = e0[j] >= r0 && e0[j] < r0 + SS_RM, in1 = e1[j] >= r0 && e1[j] < r0 + SS_RM;
+      const unsigned long long b0 = __ballot(in0), b1 = __ballot(in1);
+      const unsigned long long below = (1ull << lane) - 1ull;
+      const int rank0 = __popcll(b0 & below), rank1 = __popcll(b0) + __popcll(b1 & below);
+      // forward permutes: an in-range entry goes to the lane of its rank; the other lanes send a zero to a
+      // lane that no entry of the same permute goes to (lane 63, which only a full first vector reaches, and
+      // then every lane has an entry; for the second vector lane 0 when the ranks reach 63: the first vector
+      // then holds rank 0, or the second is full)
+      cnt[j] = __popcll(b0) + __popcll(b1);
+      const int idle1 = cnt[j] == 64 ? 0 : 63;
+      int got = 0;
+      {
+        const int a = __builtin_amdgcn_ds_permute((in0 ? rank0 : 63) * 4, in0 ? e0[j] + 1 : 0);
+        const int b = __builtin_amdgcn_ds_permute((in1 ? rank1 : idle1) * 4, in1 ? e1[j] + 1 : 0);
+        got = a | b;
+      }
+      rowsel[j] = got - 1;                              // -1 where no entry arrived
+    }
+
+    // ---- hand the row lists to the item loop through LDS (so that a slab can be picked at run time)
+    uint32_t live = 0;
+#pragma unroll
+    for (int j = 0; j < SS_BATCH; ++j) {
+      s_rows[wv][j][lane] = rowsel[j];
+      live |= cnt[j] > 0 ? 1u << j : 0u;
+    }
+    if (live == 0) continue;
+
+    // ---- one item = one 32-k step of one block (16 listed rows) of one live slab; the loads of item
+    //      t + 1 are in flight while item t is computed.  (A later block of a slab reads the slab's
+    //      rows of B again, from the L1 that the first block has just filled.)
+    struct Item { uint32_t k0, a; int c[4]; int j, b, nblk, ks; };
+    struct Regs { uint4 ra; BRow<CW> rb[8]; };
+    auto setup = [&](int j, int b, Item& T) {
+      const int* rs = s_rows[wv][j];
+      const int first = rs[0];                                  // live slab: lane 0 holds a listed row
+      const int r_a = rs[16 * b + q];
+      T.j = j; T.b = b; T.ks = 0;
+      T.nblk = (__popcll(__ballot(rs[lane] >= 0)) + 15) >> 4;   // blocks of 16 listed rows
+      T.k0 = (uint32_t)((wv + 4 * (j0 + j)) * g.slab);
+      T.a = __umul24((uint32_t)(r_a < 0 ? first : r_a), pitch_a) + 16u * (uint32_t)kb;   // unused block rows re-read a listed row
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int x = rs[16 * b + 4 * kb + e];
+        // float offset of (row, q) in the strip; unused rows: the spare row
+        T.c[e] = (((x < 0 ? SS_RM : x - r0) * (CW / 4)) * 16 + q) * 4;
+      }
+    };
+    auto loads = [&](const Item& T, Regs& R) {
+      const uint32_t k = T.k0 + 32u * (uint32_t)T.ks;
+      R.ra = load16(a_src, T.a + 2u * k);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) R.rb[i] = load_brow<CW>(b_src, b_lane + __umul24(k + (uint32_t)i, pitch_b));
+    };
+    f32x4_t acc[CW];
+    // strip element (row, column CW q + x) lives at ((row * (CW / 4) + x / 4) * 16 + q) * 4 + x % 4: a lane
+    // moves its columns of a row as 16-byte vectors, 16 lanes of a row side by side
+    auto process = [&](const Item& T, const Regs& R) {
+      if (T.ks == 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int h = 0; h < CW / 4; ++h) {
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(strip + T.c[e] + 64 * h);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[4 * h + x][e] = v[x];
+          }
+      }
+#pragma unroll
+      for (int x = 0; x < CW; ++x) acc[x] = mfma16<BF>(R.ra, bcolumn<CW>(R.rb, x), acc[x]);
+      if (T.ks == ksteps - 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int h = 0; h < CW / 4; ++h)
+            *reinterpret_cast<f32x4_t*>(strip + T.c[e] + 64 * h) =
+                f32x4_t{acc[4 * h][e], acc[4 * h + 1][e], acc[4 * h + 2][e], acc[4 * h + 3][e]};
+      }
+    };
+    // the item after T: the block's next k-step, else the slab's next block, else the next live slab.
+    // After the last item the same item is named again: its loads are issued once more and dropped, so
+    // that the loop holds no conditional load and every wait counts exactly the loads of the item after.
+    auto copy_item = [&](const Item& T, Item& N) {
+      N.k0 = T.k0; N.a = T.a; N.j = T.j; N.b = T.b; N.nblk = T.nblk; N.ks = T.ks;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) N.c[e] = T.c[e];
+    };
+    auto advance = [&](const Item& T, Item& N) -> bool {
+      if (T.ks + 1 < ksteps) { copy_item(T, N); N.ks = T.ks + 1; return true; }
+      if (T.b + 1 < T.nblk) { setup(T.j, T.b + 1, N); return true; }
+      if (live != 0) {
+        const int j = __builtin_ctz(live);
+        live &= live - 1;
+        setup(j, 0, N);
+        return true;
+      }
+      copy_item(T, N);
+      return false;
+    };
+    Item T0, T1;
+    Regs Ra, Rb;
+    {
+      const int j = __builtin_ctz(live);
+      live &= live - 1;
+      setup(j, 0, T0);
+    }
+    loads(T0, Ra);
+    for (;;) {
+      bool more = advance(T0, T1);
+      loads(T1, Rb);
+      process(T0, Ra);
+      if (!more) break;
+      more = advance(T1, T0);
+      loads(T0, Ra);
+      process(T1, Rb);
+      if (!more) break;
+    }
+  }
+  __syncthreads();
+  // the four strips in a fixed order; thread (row, q) stores CW consecutive columns
+  for (int i = tid; i < SS_RM * 16; i += 256) {
+    const int row = i >> 4, qq = i & 15;
+    if (r0 + row >= g.M) continue;
+    float* d = reinterpret_cast<float*>(g.C) + (int64_t)(r0 + row) * g.ldc + n0 + CW * qq;
+#pragma unroll
+    for (int h = 0; h < CW / 4; ++h) {
+      const int o = ((row * (CW / 4) + h) * 16 + qq) * 4;
+      const f32x4_t v = ((*reinterpret_cast<const f32x4_t*>(&s_c[0][o]) + *reinterpret_cast<const f32x4_t*>(&s_c[1][o])) +
+                         *reinterpret_cast<const f32x4_t*>(&s_c[2][o])) + *reinterpret_cast<const f32x4_t*>(&s_c[3][o]);
+      *reinterpret_cast<float4*>(d + 4 * h) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+  }
+}
+
 // Zero rows of C that no index entry names (single-segment GATHER_M): the list is ascending, so a
 // row is uncovered iff a binary search misses it.  One wave per row, 16-byte stores.
 template <int ESIZE>
@@ -837,7 +1104,6 @@ static int launch_bf(bool gather_k, int epi, int ct, const GemmArgs& g, dim3 gri
   }
   switch (epi) {
     case EPI_STORE:  return ct ? launch_one<BF, false, EPI_STORE, 1>(g, grid, st) : launch_one<BF, false, EPI_STORE, 0>(g, grid, st);
-    case EPI_ATOMIC: return ct ? PIT_EINVAL : launch_one<BF, false, EPI_ATOMIC, 0>(g, grid, st);
     case EPI_GELU:   return ct ? launch_one<BF, false, EPI_GELU, 1>(g, grid, st) : PIT_EINVAL;
     default: return PIT_EINVAL;
   }
@@ -918,8 +1184,17 @@ extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void
     return launch_sread_gemm(in_dt == PIT_BF16, false, EPI_STORE, c_dt != PIT_F32, g, tiles_per_seg, st);
   }
   if (c_dt != PIT_F32) return PIT_EINVAL;
-  { const int rc = launch_zero_rows(d_C, ldc * 4, M, (int64_t)N * 4, st); if (rc != PIT_OK) return rc; }
-  const int64_t max_tiles = (int64_t)ix->nseg * tiles_per_seg;
-  if (max_tiles > 65535) return PIT_ESHAPE;
-  return launch_sread_gemm(in_dt == PIT_BF16, false, EPI_ATOMIC, 0, g, (int)max_tiles, st);
+  // several k-slabs per row: C-stationary strips (every element of C is written, nothing to clear)
+  if (g.lda * 2 >= (1ll << 24) || g.ldb * 2 >= (1ll << 24) || (int64_t)M >= (1ll << 24) || (int64_t)K >= (1ll << 24)) return PIT_ESHAPE;
+  if ((int64_t)M * g.lda * 2 >= (1ll << 32) || (int64_t)K * g.ldb * 2 >= (1ll << 32)) return PIT_ESHAPE;
+  // 32 x 128 strips.  (64 x 64 strips, CW = 4, halve the traffic of B and double that of A: measured 10-15 %
+  // faster at 90-95 % sparsity of a 4096^3 product, 10-20 % slower at 50 % and at 99 %.)
+  constexpr int CW = 8;
+  const int64_t strips = ceil_div(M, StripShape<CW>::R);
+  if (strips > 65535 || N % StripShape<CW>::W) return PIT_ESHAPE;
+  dim3 grid((unsigned)(N / StripShape<CW>::W), (unsigned)strips);
+  if (in_dt == PIT_BF16) hipLaunchKernelGGL((k_slab_strip<true, CW>), grid, dim3(256), 0, st, g);
+  else                   hipLaunchKernelGGL((k_slab_strip<false, CW>), grid, dim3(256), 0, st, g);
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
 }

@@ -17,8 +17,8 @@
 //             row); the 16-byte chunk index is XOR-ed with ((m >> 1) & 7) so that 16 consecutive
 //             rows hit 16 different 16-byte slots of the 256-byte bank row.
 // SWrite.  The epilogue stores accumulator rows to the row numbers held in LDS (identity or the
-// index), optionally through fp32 atomics (several k-slabs accumulate into one C), a GELU + round
-// to the input type (first MoE matmul) or a per-row gate (second MoE matmul).
+// index), optionally with a GELU + round to the input type (first MoE matmul) or a per-row gate
+// (second MoE matmul).
 #pragma once
 #include "pit_common.hpp"
 
@@ -29,6 +29,7 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef short v4i16_t __attribute__((__vector_size__(8)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 #define PIT_LDS __attribute__((address_space(3)))
 
 constexpr int TM = 128, TN = 128, TK = 64;
@@ -36,7 +37,7 @@ constexpr int A_TILE_BYTES = TM * TK * 2;   // 16 KiB either layout
 constexpr int B_TILE_BYTES = TK * TN * 2;   // 16 KiB
 constexpr int STAGE_BYTES = A_TILE_BYTES + B_TILE_BYTES;
 
-enum { EPI_STORE = 0, EPI_ATOMIC = 1, EPI_GELU = 2 };
+enum { EPI_STORE = 0, EPI_GELU = 2 };
 
 struct GemmArgs {
   const void* A; int64_t lda;

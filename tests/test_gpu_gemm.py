@@ -247,6 +247,62 @@ def test_c1_full_size(pit):
     assert_close(C, orc.gemm(w.A, w.B), "C1 full size")
 
 
+@pytest.mark.parametrize("M,K,N,mt,p", [
+    (96, 32 * 70, 128, 32, 0.3),        # 70 slabs: 17-18 per wave, three batches of row lookups
+    (9000, 128, 128, 32, 0.7),          # lists of ~6300 rows: two rounds of the 64-ary search
+    (5000, 192, 256, 64, 0.95),         # nearly full strips (two blocks of 16 rows), ragged last strip
+    (33, 256, 128, 128, 0.5),           # slabs of four k-steps, a single row in the second strip
+])
+def test_microtile_long_lists_many_slabs(pit, M, K, N, mt, p):
+    w = wl.microtile_gemm(M=M, K=K, N=N, mt_k=mt, p_keep=p, seed=M + K, integer=True)
+    C = _run_microtile(pit, w, mt=mt)
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm(w.A, w.B))
+
+
+def test_microtile_clustered_rows(pit):
+    """Live micro-tiles bunched in a few row ranges: long runs of listed rows in some strips, none in
+    most, and lists whose first entry lies far above the first strips."""
+    g = np.random.default_rng(77)
+    M, K, N, mt = 4096, 256, 128, 32
+    A = g.integers(-4, 5, size=(M, K)).astype(np.float16)
+    keep = np.zeros((M, K // mt), dtype=bool)
+    for s in range(K // mt):
+        start = int(g.integers(0, M - 300))
+        keep[start:start + int(g.integers(1, 300)), s] = True
+    keep[M - 1, :] = True
+    keep[:, 3] = False                                                # one slab lists nothing
+    A = (A.reshape(M, K // mt, mt) * keep[:, :, None]).reshape(M, K).astype(np.float16)
+    B = g.integers(-4, 5, size=(K, N)).astype(np.float16)
+    C = _run_microtile(pit, wl.MicroTileGemm(A=A, B=B, keep=keep, mt_k=mt))
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm(A, B))
+
+
+def test_microtile_bf16_strided_and_reproducible(pit):
+    """bf16 inputs, operands and output with leading dimensions larger than their rows; two runs give
+    the same bits (the slabs' partial sums are added in a fixed order), and the columns of the output
+    buffer beyond N stay as they were."""
+    g = np.random.default_rng(9)
+    M, K, N, mt = 700, 512, 256, 32
+    keep = g.random((M, K // mt)) < 0.15
+    Af = (g.standard_normal((M, K)).astype(np.float32).reshape(M, K // mt, mt) * keep[:, :, None]).reshape(M, K)
+    A_full = np.zeros((M, K + 64), dtype=np.uint16)
+    A_full[:, :K] = wl.to_bf16_bits(Af)
+    A_full[:, K:] = 0x7fc0                                           # NaN beyond the operand: must not be read into the product
+    B_full = np.full((K, N + 128), 0x7fc0, dtype=np.uint16)
+    B_full[:, :N] = wl.to_bf16_bits(g.standard_normal((K, N)).astype(np.float32))
+    tA, tB = to_dev(A_full), to_dev(B_full)
+    ix = pit.pit_build_index(tA[:, :K], 1, mt, 0)
+    outs = []
+    for _ in range(2):
+        C = torch.full((M, N + 32), -7.0, device=dev())
+        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, tA[:, :K], tB[:, :N], ix, mt, M, N, K, out=C[:, :N])
+        torch.cuda.synchronize()
+        outs.append(C)
+    assert torch.equal(outs[0], outs[1])
+    assert bool((outs[0][:, N:] == -7.0).all())
+    assert_close(outs[0][:, :N], orc.gemm(A_full[:, :K].copy(), B_full[:, :N].copy()), "k-slab bf16 strided")
+
+
 def test_microtile_all_zero(pit):
     w = wl.microtile_gemm(M=128, K=64, N=128, p_keep=0.0, seed=1)
     C = _run_microtile(pit, w)
