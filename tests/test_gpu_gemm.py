@@ -207,6 +207,24 @@ def test_padded_linear_degenerate_masks(pit):
         assert np.array_equal(Y.cpu().numpy().astype(np.float64), orc.gemm_rows_masked(w.X, w.row_mask, w.W))
 
 
+def test_padded_linear_bf16_output(pit):
+    """Output in the input type (what the next layer of a bf16 model reads): listed rows within one bf16
+    ulp of the rounded oracle, padding rows exactly zero, also from a sentinel-filled buffer."""
+    w = wl.padded_linear(batch=5, max_len=100, hidden=192, out=256, min_len=1, seed=12)
+    X, W, mask = to_dev(w.X), to_dev(w.W), to_dev(w.row_mask.reshape(-1, 1))
+    M, K = w.X.shape
+    N = w.W.shape[1]
+    ix = pit.pit_build_index(mask, 1, 1, 0)
+    out = torch.full((M, N), 3.0, dtype=torch.bfloat16, device=dev())
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=out, zero_uncovered=True)
+    torch.cuda.synchronize()
+    ref = orc.gemm_rows_masked(w.X, w.row_mask, w.W)
+    got = orc.bf16_bits_to_f64(bf16_bits(out))
+    want = orc.round_to_bf16(ref)
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -7 + 1e-30)
+    assert not got[w.row_mask == 0].any()
+
+
 def test_c4_full_size(pit):
     w = wl.padded_linear()
     Y = _run_padded(pit, w, sentinel=7.0)
