@@ -328,12 +328,6 @@ k_gather_m(const GemmArgs g) {
       bf[i] = lds_read_frag(t + rd_b[i][ks]);
     }
   };
-  auto mfma4 = [&](const u32x4_t (&af)[2], const u32x4_t (&bf)[2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<BF>(af[i], bf[j], acc[i][j]);
-  };
   // One step.  MFMAs of `step` read LDS buffer `buf`; the tile of step + 1, already transposed in
   // the registers o[], goes to the other buffer; the tile of step + 2 is taken out of ring slot r
   // and transposed into o[]; the loads of step + 1 + D refill ring slot rl (the one emptied by the
@@ -353,7 +347,9 @@ k_gather_m(const GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int ks = i >> 2, q = i & 3;
-      acc[q >> 1][q & 1] = mfma32<BF>(fa[ks & 1][q >> 1], fb[ks & 1][q & 1], acc[q >> 1][q & 1]);
+      // operands swapped: the accumulator holds the 32 x 32 block transposed (lane = row of C, registers =
+      // columns, four consecutive ones at a time), which is what the stores below want
+      acc[q >> 1][q & 1] = mfma32<BF>(fb[ks & 1][q & 1], fa[ks & 1][q >> 1], acc[q >> 1][q & 1]);
       if (i < 12) {   // operands of k-substep ks + 1: A block 0, B block 0, A block 1, B block 1
         const int nb = (ks + 1) & 1;
         if (q == 0) fa[nb][0] = lds_read_frag(t + rd_a[0][ks + 1]);
@@ -407,25 +403,34 @@ k_gather_m(const GemmArgs g) {
   }
 
   // ---------------------------------------------------------------- SWrite
+  // lane l holds row (l % 32) of each of its two row blocks and, per register quad, 4 consecutive
+  // columns: one row number and (optionally) one gate value per lane and block, 16-byte stores
+  // (8-byte ones for 16-bit output), 16 store instructions per wave instead of 64 scalar ones
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
+    const int r = wm * 64 + i * 32 + (lane & 31);
+    const int64_t crow = s_rows_c[r];
+    if (crow < 0) continue;
+    float scale = 1.f;
+    if constexpr (EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int r = wm * 64 + i * 32 + 8 * (e >> 2) + (lane >> 5) * 4 + (e & 3);
-      const int64_t crow = s_rows_c[r];
-      if (crow < 0) continue;
-      float scale = 1.f;
-      if constexpr (EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
+    for (int j = 0; j < 2; ++j) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-        float v = acc[i][j][e];
-        if constexpr (EPI == EPI_GELU) v = gelu_erf_fast(v);
-        if constexpr (EPI == EPI_STORE) v *= scale;
+      for (int gq = 0; gq < 4; ++gq) {
+        const int col = n0 + wn * 64 + j * 32 + 8 * gq + 4 * (lane >> 5);
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          v[x] = acc[i][j][4 * gq + x];
+          if constexpr (EPI == EPI_GELU) v[x] = gelu_erf_fast(v[x]);
+          if constexpr (EPI == EPI_STORE) v[x] *= scale;
+        }
         if constexpr (CT == 0) {
-          reinterpret_cast<float*>(g.C)[crow * g.ldc + col] = v;
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C) + crow * g.ldc + col) = make_float4(v[0], v[1], v[2], v[3]);
         } else {
-          reinterpret_cast<uint16_t*>(g.C)[crow * g.ldc + col] = f32_to_in<BF>(v);
+          const uint32_t lo = (uint32_t)f32_to_in<BF>(v[0]) | ((uint32_t)f32_to_in<BF>(v[1]) << 16);
+          const uint32_t hi = (uint32_t)f32_to_in<BF>(v[2]) | ((uint32_t)f32_to_in<BF>(v[3]) << 16);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.C) + crow * g.ldc + col) = make_uint2(lo, hi);
         }
       }
     }
