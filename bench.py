@@ -123,6 +123,24 @@ def bench_relu_ffn(pit, wl, steps, warmup, pool=8, with_cpu=True):
     kernel_ms = float(np.mean([kev[2 * gi].elapsed_time(kev[2 * gi + 1]) for gi in range(groups)])) / per_group
     eff = float(np.mean([eff_flops[(warmup + i) % pool] for i in range(steps)]))
 
+    # what the gather costs: the same kernel on an index with the same list lengths whose lists are
+    # 0, 1, 2, ... (contiguous k instead of the scattered live channels)
+    sp = ix.seg_ptr.to(torch.int64)
+    nnz = int(sp[-1].item())
+    seg_of = torch.repeat_interleave(torch.arange(M // MT, device="cuda"), (sp[1:] - sp[:-1]))
+    ident = pit.PitIndex(ix.seg_ptr.clone(), (torch.arange(nnz, device="cuda") - sp[seg_of]).to(torch.int32), None, ix.nseg, nnz)
+    # (groups of launches with the two indices alternate, so that both see the same clocks)
+    iev = _events(4 * groups)
+    for gi in range(groups):
+        for which, index in enumerate((ident, ix)):
+            iev[4 * gi + 2 * which].record()
+            for _ in range(per_group):
+                pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xts[last], W, index, MT, M, N, K, out=C)
+            iev[4 * gi + 2 * which + 1].record()
+    torch.cuda.synchronize()
+    ident_ms = float(np.mean([iev[4 * gi].elapsed_time(iev[4 * gi + 1]) for gi in range(groups)])) / per_group
+    real_ms = float(np.mean([iev[4 * gi + 2].elapsed_time(iev[4 * gi + 3]) for gi in range(groups)])) / per_group
+
     # dense comparator at the same shape: hipBLASLt through torch.matmul on a row-major copy of X
     X = Xts[0].t().contiguous()
     for _ in range(5):
@@ -137,7 +155,7 @@ def bench_relu_ffn(pit, wl, steps, warmup, pool=8, with_cpu=True):
 
     res = {
         "sec_per_step": sec, "eff_flops": eff, "index_ms": float(idx_ms), "gemm_ms": float(gemm_ms),
-        "gemm_kernel_ms": kernel_ms, "gemm_kernel_flops": eff_flops[last],
+        "gemm_kernel_ms": kernel_ms, "gemm_kernel_flops": eff_flops[last], "gemm_kernel_identity_index_ms": ident_ms, "gemm_kernel_interleaved_ms": real_ms,
         "dense_ms": float(dense_ms), "dense_flops": 2.0 * M * K * N,
     }
     if with_cpu:
@@ -431,6 +449,8 @@ def main():
         "index_build_ms": round(r["index_ms"], 4), "gemm_ms": round(r["gemm_ms"], 4),
         "index_build_GB_per_s": round(2.0 * 2048 * 8192 / (r["index_ms"] * 1e-3) / 1e9, 1),   # the tensor read once
         "gemm_kernel_ms": round(r["gemm_kernel_ms"], 4),
+        "gemm_kernel_identity_index_ms": round(r["gemm_kernel_identity_index_ms"], 4),
+        "gather_overhead": round(1.0 - r["gemm_kernel_identity_index_ms"] / r["gemm_kernel_interleaved_ms"], 4),
         "index_share_of_step": round(r["index_ms"] / (r["index_ms"] + r["gemm_ms"]), 4),
         "roofline": {"bound": "mfma", "kernel": "k_gather_k_direct (bf16)", "achieved": round(gemm_tflops, 2),
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / MFMA_PEAK_TFLOPS, 4),
