@@ -111,6 +111,7 @@ def bench_relu_ffn(pit, wl, steps, warmup, pool=8, with_cpu=True):
     torch.cuda.synchronize()
     idx_ms = np.mean([ev[3 * i].elapsed_time(ev[3 * i + 1]) for i in range(steps)])
     gemm_ms = np.mean([ev[3 * i + 1].elapsed_time(ev[3 * i + 2]) for i in range(steps)])
+    step_ev = np.array([ev[3 * i].elapsed_time(ev[3 * i + 2]) for i in range(steps)])   # (event pairs include the dispatch gaps)
     last = (warmup + steps - 1) % pool
     groups, per_group = max(2, steps // 8), 8
     kev = _events(2 * groups)
@@ -155,6 +156,7 @@ def bench_relu_ffn(pit, wl, steps, warmup, pool=8, with_cpu=True):
 
     res = {
         "sec_per_step": sec, "eff_flops": eff, "index_ms": float(idx_ms), "gemm_ms": float(gemm_ms),
+        "step_event_ms_p10_p50_p90": [round(float(np.percentile(step_ev, q)), 4) for q in (10, 50, 90)],
         "gemm_kernel_ms": kernel_ms, "gemm_kernel_flops": eff_flops[last], "gemm_kernel_identity_index_ms": ident_ms, "gemm_kernel_interleaved_ms": real_ms,
         "dense_ms": float(dense_ms), "dense_flops": 2.0 * M * K * N,
     }
@@ -447,6 +449,7 @@ def main():
         "speedup_vs_dense": round(r["dense_ms"] / (sec * 1e3), 3),
         "dense_gemm_ms": round(r["dense_ms"], 4),
         "index_build_ms": round(r["index_ms"], 4), "gemm_ms": round(r["gemm_ms"], 4),
+        "step_event_ms_p10_p50_p90": r["step_event_ms_p10_p50_p90"],
         "index_build_GB_per_s": round(2.0 * 2048 * 8192 / (r["index_ms"] * 1e-3) / 1e9, 1),   # the tensor read once
         "gemm_kernel_ms": round(r["gemm_kernel_ms"], 4),
         "gemm_kernel_identity_index_ms": round(r["gemm_kernel_identity_index_ms"], 4),
