@@ -411,6 +411,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--only-headline", action="store_true", help="skip the other synthetic workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--side", default=None,
+                    help="run ONE of the other synthetic workloads alone (for profiling its kernels) and print its "
+                         "summary instead of the headline line, e.g. --side padded_batch_32x512")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one elementwise kernel that reads and writes 256 MiB, as the known-size "
                          "reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -432,6 +435,17 @@ def main():
         torch.mul(src, 2.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+    side = [("relu_ffn_correlated_zeros", bench_relu_ffn_correlated),
+            ("relu_ffn_from_preactivation", bench_relu_producer),
+            ("microtile_1x32_1024", bench_microtile), ("moe_switch_4096x64", bench_moe),
+            ("padded_batch_32x512", bench_padded_linear), ("sparse_attn_4096x12x64", bench_attn)]
+    if args.side is not None:
+        fns = dict(side)
+        if args.side not in fns:
+            print("bench.py: --side must be one of " + ", ".join(fns), file=sys.stderr)
+            sys.exit(2)
+        print(json.dumps({"workload": args.side, **_summary(fns[args.side](pit, wl, args.steps, args.warmup))}))
+        return
     r = bench_relu_ffn(pit, wl, args.steps, args.warmup, with_cpu=not args.no_cpu)
     sec = r["sec_per_step"]
     value = r["eff_flops"] / sec / 1e12
@@ -465,10 +479,7 @@ def main():
     if not args.only_headline:
         others = {}
         k, w_ = max(5, args.steps // 2), max(2, args.warmup // 2)
-        for name, fn in [("relu_ffn_correlated_zeros", bench_relu_ffn_correlated),
-                         ("relu_ffn_from_preactivation", bench_relu_producer),
-                         ("microtile_1x32_1024", bench_microtile), ("moe_switch_4096x64", bench_moe),
-                         ("padded_batch_32x512", bench_padded_linear), ("sparse_attn_4096x12x64", bench_attn)]:
+        for name, fn in side:
             if name.startswith("sparse_attn") and not hasattr(pit._lib, "pit_sparse_attn"):
                 continue
             try:
