@@ -824,6 +824,53 @@ static int launch_bitmap_tiles(const Layout& L, const void* d_src, int esize, in
   return PIT_OK;
 }
 
+// A byte mask over rows (one column, 1 x 1 micro-tiles, a single segment: which token rows of a padded
+// batch are valid) of at most 65536 rows is small enough for ONE workgroup to do everything, in one
+// launch instead of two: thread t takes `per` consecutive rows (one 16-byte load when the mask is
+// contiguous), counts them, a scan over the workgroup gives its position in the list, and it writes
+// its row numbers there in ascending order.  Same result as the two-pass path, bit for bit.
+__global__ void __launch_bounds__(1024) k_index_rowmask(const uint8_t* __restrict__ src, int64_t ld, int rows,
+                                                        int32_t* __restrict__ seg_ptr, int32_t* __restrict__ idx) {
+  __shared__ int s_wave[16];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int per = (rows + 1023) / 1024;          // <= 64
+  const int r0 = tid * per;
+  u64 flags = 0;
+  if (ld == 1 && per == 16 && (reinterpret_cast<uintptr_t>(src) & 15) == 0 && r0 + 16 <= rows) {
+    const uint4 v = *reinterpret_cast<const uint4*>(src + r0);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if ((w[i >> 2] >> (8 * (i & 3))) & 0xffu) flags |= 1ull << i;
+  } else {
+    for (int i = 0; i < per; ++i)
+      if (r0 + i < rows && src[(int64_t)(r0 + i) * ld] != 0) flags |= 1ull << i;
+  }
+  const int c = __popcll(flags);
+  int inc = c;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  if (lane == 63) s_wave[wv] = inc;
+  __syncthreads();
+  int base = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int x = s_wave[w];
+    if (w < wv) base += x;
+    total += x;
+  }
+  int pos = base + inc - c;
+  while (flags) {
+    const int b = __builtin_ctzll(flags);
+    flags &= flags - 1;
+    idx[pos++] = r0 + b;
+  }
+  if (tid == 0) { seg_ptr[0] = 0; seg_ptr[1] = total; }
+}
+
 // pass 1: the bitmap of non-empty micro-tiles (and, if occ != nullptr, their element occupancy)
 static int launch_bitmap(const Layout& L, const void* d_src, int esize, int rows, int cols, int64_t ld,
                          int mt_rows, int mt_cols, int pit_dim, bool want_bits, u64* words, uint32_t* occ,
@@ -879,6 +926,13 @@ extern "C" int pit_build_index(const void* d_src, int dt, int rows, int cols, in
   if (L.nseg == 0 || L.npit == 0) return launch_emit(L, nullptr, nullptr, nullptr, out, 0, nullptr, st);
   if (!d_src || !out->idx || !d_ws || !aligned(d_ws, 8) || !aligned(d_src, esize)) return PIT_EINVAL;
   if (ws_bytes < pit_build_index_workspace(rows, cols, mt_rows, mt_cols, pit_dim, want_bits)) return PIT_ECAPACITY;
+
+  if (esize == 1 && cols == 1 && mt_rows == 1 && mt_cols == 1 && pit_dim == 0 && !want_bits && rows <= 65536) {
+    hipLaunchKernelGGL(k_index_rowmask, dim3(1), dim3(1024), 0, st, reinterpret_cast<const uint8_t*>(d_src), ld, rows,
+                       out->seg_ptr, out->idx);
+    PIT_LAUNCH_CHECK();
+    return PIT_OK;
+  }
 
   char* ws = reinterpret_cast<char*>(d_ws);
   u64* words = reinterpret_cast<u64*>(ws);

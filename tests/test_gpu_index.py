@@ -51,6 +51,23 @@ def test_c4_row_mask_full_size(pit):
     assert int(ix.seg_ptr[-1]) == int(w.lengths.sum())
 
 
+@pytest.mark.parametrize("rows", [1, 15, 16, 17, 1000, 1024, 16384, 40000, 65536, 65537, 100000])
+@pytest.mark.parametrize("density", [0.0, 0.5, 1.0])
+def test_row_mask_of_any_length(pit, rows, density):
+    """A byte mask over rows (one column): up to 65536 rows one launch builds the whole index, longer
+    masks take the two passes; contiguous and strided masks, any non-zero byte counts."""
+    g = np.random.default_rng(rows + int(density * 10))
+    mask = (g.random(rows) < density).astype(np.uint8) * g.integers(1, 256, size=rows).astype(np.uint8)
+    want = orc.build_index(mask.reshape(-1, 1), 1, 1, 0)
+    assert_index_equal(pit.pit_build_index(to_dev(mask.reshape(-1, 1)), 1, 1, 0), want)
+    wide = torch.zeros((rows, 3), dtype=torch.uint8, device=dev())
+    wide[:, 1] = to_dev(mask)
+    assert_index_equal(pit.pit_build_index(wide[:, 1:2], 1, 1, 0), want)      # stride 3 between rows
+    if rows > 1:
+        off = to_dev(np.concatenate([np.zeros(1, np.uint8), mask]))[1:].reshape(-1, 1)   # not 16-byte aligned
+        assert_index_equal(pit.pit_build_index(off, 1, 1, 0), want)
+
+
 def test_c5_attention_mask_full_size_with_bits(pit):
     w = wl.sparse_attn(H=1, D=8)
     _check(pit, w.mask, 32, 1, 1, want_bits=True)
