@@ -199,7 +199,11 @@ typedef enum pit_gemm_mode {
    * (Section 3.2).  Micro-tile = mt consecutive m (one k): the index has nseg = M / mt
    * segments, segment s listing the k whose micro-tile At[k, s*mt .. (s+1)*mt) is non-zero.
    * C[s*mt .. (s+1)*mt, :] = sum over listed k of At[k, rows]^T . B[k, :].  Plain stores; every
-   * element of C is written.  mt must be 128 (the dense tile height of this kernel).
+   * element of C is written.  mt is 128, 64 or 32: the dense tile is mt rows x 128 columns (paper
+   * Section 3.2: the micro-tile takes the dense tile's extent on the other axes).  A lower tile
+   * follows a finer sparsity pattern -- fewer all-zero micro-tiles are multiplied (Table 3, "sparsity
+   * ratio after cover") -- and reads B once per mt rows of C instead of once per 128; which one is
+   * cheaper for given data is what pit_select_kernel decides.
    */
   PIT_GEMM_GATHER_K = 1
 } pit_gemm_mode;
@@ -210,7 +214,7 @@ typedef enum pit_gemm_mode {
  *          fp32 accumulator, nearest-even; not available when nseg > 1 in GATHER_M mode).
  *   ix     index built by pit_build_index on A (or on a row mask) with the micro-tile named above.
  * Shape rules (else PIT_ESHAPE): N % 128 == 0; GATHER_M: mt % 32 == 0 and K % mt == 0;
- * GATHER_K: mt == 128, M % 128 == 0.  Pointers 16-byte aligned, leading dimensions % 8 == 0.
+ * GATHER_K: mt in {32, 64, 128}, M % mt == 0.  Pointers 16-byte aligned, leading dimensions % 8 == 0.
  * Index entries outside the valid coordinate range are a caller error (not checked on the device).
  */
 int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void* d_B, int64_t ldb,
@@ -257,6 +261,9 @@ size_t pit_sparse_attn_workspace(int H, int S, int D);
  *           The index is detected online at 32 x 1 granularity (32 queries x 1 key); inside a kept
  *           micro-tile the element mask is honoured exactly.  A query with no allowed key gives a
  *           zero row.
+ * Precision: scores, softmax and accumulation in fp32.  V enters the second product in its own type
+ * (every finite bf16 / fp16 value as it is: no range restriction); the softmax numerators enter it as
+ * a two-term bf16 sum (relative error < 2^-15) for bf16 inputs and rounded to fp16 for fp16 inputs.
  * Shape rules: D == 64, S % 32 == 0.
  */
 int pit_sparse_attn(const void* d_Q, const void* d_K, const void* d_V, const uint8_t* d_mask,

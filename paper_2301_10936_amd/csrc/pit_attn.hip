@@ -14,15 +14,17 @@
 //                row is d-contiguous, which is what the A operand wants).
 //        S^T   = K' . Q^T           4 x v_mfma_f32_32x32x16 (input type), fp32
 //        mask, running max / sum per query, P^T = exp2(S^T*c - m)        fp32, in registers
-//        O^T  += V'^T . P^T         4 x v_mfma_f32_32x32x16_f16; V'^T operands come from LDS with
-//                the transposing read; the accumulator layout of S^T is already the B-operand
-//                layout of this product up to a permutation of the keys inside the chunk, which is
-//                free because keys are a PIT-axis here (the same permutation is applied to V').
+//        O^T  += V'^T . P^T         v_mfma_f32_32x32x16 in the input type; V'^T operands come from
+//                LDS with the transposing read; the accumulator layout of S^T is already the
+//                B-operand layout of this product up to a permutation of the keys inside the chunk,
+//                which is free because keys are a PIT-axis here (the same permutation is applied to V').
 //      SWrite is a plain store: queries of a block are contiguous.
-// P and V enter the second product as fp16 (11-bit significand): bf16 P would by itself cost about
-// 1.7e-3 relative Frobenius error.  bf16 V converts to fp16 exactly for 2^-24 <= |v| <= 65504
-// (smaller magnitudes lose bits or flush, larger overflow; neither occurs for activations of
-// order 1).
+// Precision of P in the second product: P rounded to bf16 would by itself cost about 1.7e-3 relative
+// Frobenius error.  With fp16 inputs P is rounded to fp16 (11-bit significand, 4 MFMAs per chunk).
+// With bf16 inputs V stays bf16 -- every finite bf16 value is used as it is, no range restriction --
+// and P enters as the sum of two bf16 terms, P = hi + lo with hi = P truncated to bf16 and lo = the
+// exact fp32 remainder rounded to bf16 (relative error of the pair below 2^-15), in 8 MFMAs per chunk
+// that share their V operands.
 #include "pit_common.hpp"
 
 namespace pit {
@@ -47,16 +49,18 @@ __device__ __forceinline__ f32x16_t mfma_in(const uint4& a, const uint4& b, cons
   else
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
-__device__ __forceinline__ f32x16_t mfma_f16(const uint4& a, const uint4& b, const f32x16_t& c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
-}
 __device__ __forceinline__ uint32_t pack_f16x2(float a, float b) {
   const uint16_t lo = __builtin_bit_cast(uint16_t, (_Float16)a), hi = __builtin_bit_cast(uint16_t, (_Float16)b);
   return (uint32_t)lo | ((uint32_t)hi << 16);
 }
-__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t v) {
-  const float lo = __builtin_bit_cast(float, v << 16), hi = __builtin_bit_cast(float, v & 0xFFFF0000u);
-  return pack_f16x2(lo, hi);
+// a, b >= 0 (softmax numerators).  hi2 = {a, b} truncated to bf16; lo2 = the remainders a - hi(a), b - hi(b)
+// (exact in fp32) rounded to bf16 (half up on the magnitude; they are >= 0).  hi + lo reproduces the fp32
+// value to 2^-15 relative.
+__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t& hi2, uint32_t& lo2) {
+  const uint32_t ua = __builtin_bit_cast(uint32_t, a), ub = __builtin_bit_cast(uint32_t, b);
+  hi2 = __builtin_amdgcn_perm(ub, ua, 0x07060302u);
+  const float ra = a - __builtin_bit_cast(float, ua & 0xFFFF0000u), rb = b - __builtin_bit_cast(float, ub & 0xFFFF0000u);
+  lo2 = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, rb) + 0x8000u, __builtin_bit_cast(uint32_t, ra) + 0x8000u, 0x07060302u);
 }
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
@@ -164,12 +168,7 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int x = it * 64 + lane;
-      uint4 v = vr[it];
-      if constexpr (BF) {
-        v.x = bf16x2_to_f16x2(v.x); v.y = bf16x2_to_f16x2(v.y);
-        v.z = bf16x2_to_f16x2(v.z); v.w = bf16x2_to_f16x2(v.w);
-      }
-      *(PIT_LDS u32x4_t*)(uintptr_t)(v_lds + v_off(x >> 3, x & 7)) = __builtin_bit_cast(u32x4_t, v);
+      *(PIT_LDS u32x4_t*)(uintptr_t)(v_lds + v_off(x >> 3, x & 7)) = __builtin_bit_cast(u32x4_t, vr[it]);
     }
     // K tile [32 keys][8 chunks of 16 B], chunk index XOR-ed with (key >> 1) & 7: the straight writes
     // and the operand reads (lane: key ql, chunk 2 ks + h) are both free of bank conflicts
@@ -227,11 +226,19 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
       // O^T += V'^T . P^T ; k-step t covers chunk keys 16t .. 16t+15 in the order the accumulator holds them
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        uint4 pb;
-        pb.x = pack_f16x2(st[8 * t + 0], st[8 * t + 1]);
-        pb.y = pack_f16x2(st[8 * t + 2], st[8 * t + 3]);
-        pb.z = pack_f16x2(st[8 * t + 4], st[8 * t + 5]);
-        pb.w = pack_f16x2(st[8 * t + 6], st[8 * t + 7]);
+        uint4 pb, pl = make_uint4(0, 0, 0, 0);
+        if constexpr (BF) {
+          uint32_t hi2[4], lo2[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) split_bf16x2(st[8 * t + 2 * x], st[8 * t + 2 * x + 1], hi2[x], lo2[x]);
+          pb = make_uint4(hi2[0], hi2[1], hi2[2], hi2[3]);
+          pl = make_uint4(lo2[0], lo2[1], lo2[2], lo2[3]);
+        } else {
+          pb.x = pack_f16x2(st[8 * t + 0], st[8 * t + 1]);
+          pb.y = pack_f16x2(st[8 * t + 2], st[8 * t + 3]);
+          pb.z = pack_f16x2(st[8 * t + 4], st[8 * t + 5]);
+          pb.w = pack_f16x2(st[8 * t + 6], st[8 * t + 7]);
+        }
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt) {
           const int r0 = 16 * t + 4 * h + ((lane & 15) >> 2);
@@ -241,7 +248,9 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
           const uint32_t a1 = v_lds + (uint32_t)(r1 * 128 + ((((col >> 5) ^ ((r1 >> 1) & 1)) << 6) | ((col & 31) * 2)));
           const uint2 lo = __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((PIT_LDS v4i16_t*)(uintptr_t)a0));
           const uint2 hi = __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((PIT_LDS v4i16_t*)(uintptr_t)a1));
-          o[dt] = mfma_f16(make_uint4(lo.x, lo.y, hi.x, hi.y), pb, o[dt]);
+          const uint4 vt = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          o[dt] = mfma_in<BF>(vt, pb, o[dt]);
+          if constexpr (BF) o[dt] = mfma_in<BF>(vt, pl, o[dt]);
         }
       }
     }

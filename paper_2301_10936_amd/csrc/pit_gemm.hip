@@ -94,6 +94,14 @@ __device__ __forceinline__ uint32_t transpose8x8_dword(const uint4 (&r)[8], int 
   const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
   return __builtin_amdgcn_perm(b, a, sel);
 }
+// JA consecutive 16-bit columns of one k-row as loaded (JA = 8: 16 bytes, 4: 8 bytes, 2: 4 bytes)
+template <int JA> struct ACols { uint32_t d[JA / 2]; };
+// Dword jj (k = 2 jj, 2 jj + 1) of column x out of 8 k-rows of JA columns each (one v_perm_b32).
+template <int JA>
+__device__ __forceinline__ uint32_t transpose_cols_dword(const ACols<JA> (&r)[8], int x, int jj) {
+  const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
+  return __builtin_amdgcn_perm(r[2 * jj + 1].d[x >> 1], r[2 * jj].d[x >> 1], sel);
+}
 // One output row of the 8 x 8 transpose below: out_x = 8 consecutive k of column x (4 v_perm_b32).
 __device__ __forceinline__ uint4 transpose8x8_row(const uint4 (&r)[8], int x) {
   const int i = x >> 1;
@@ -137,6 +145,23 @@ __device__ __forceinline__ uint4 load16(const char* base, uint32_t byte_off) {
   typedef const u32x4_t __attribute__((address_space(1))) * gptr_t;
   const u32x4_t v = *(gptr_t)(uintptr_t)(reinterpret_cast<uintptr_t>(base) + byte_off);
   return __builtin_bit_cast(uint4, v);
+}
+// the same for 2 * JA bytes
+template <int JA>
+__device__ __forceinline__ ACols<JA> load_cols(const char* base, uint32_t byte_off) {
+  ACols<JA> r;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(base) + byte_off;
+  if constexpr (JA == 8) {
+    const u32x4_t v = *(const u32x4_t __attribute__((address_space(1)))*)a;
+    r.d[0] = v[0]; r.d[1] = v[1]; r.d[2] = v[2]; r.d[3] = v[3];
+  } else if constexpr (JA == 4) {
+    const u32x2_t v = *(const u32x2_t __attribute__((address_space(1)))*)a;
+    r.d[0] = v[0]; r.d[1] = v[1];
+  } else {
+    static_assert(JA == 2, "columns per lane");
+    r.d[0] = *(const uint32_t __attribute__((address_space(1)))*)a;
+  }
+  return r;
 }
 
 // nothing may be scheduled across this point
@@ -505,37 +530,39 @@ __device__ __forceinline__ void red_recv(f32x4_t (&acc)[8][8], PIT_LDS char* buf
     PIT_SCHED_FENCE();
   }
 }
-// Two-wave workgroups: half H of the tile = the row groups ja in {4H .. 4H + 3}.
-constexpr int RED_HALF_BYTES = 32 * 64 * 16;
-template <int H>
-__device__ __forceinline__ void red_send_half(const f32x4_t (&acc)[8][8], PIT_LDS char* slot) {
+// Two-wave workgroups: half H of the tile = the row groups ja in {H * JA / 2 .. (H + 1) * JA / 2 - 1}
+// (JA = row groups of the tile = tile rows / 16).
+template <int JA> constexpr int red_half_bytes() { return 4 * JA * 64 * 16; }
+template <int JA, int H>
+__device__ __forceinline__ void red_send_half(const f32x4_t (&acc)[JA][8], PIT_LDS char* slot) {
 #pragma unroll
-  for (int i = 0; i < 32; ++i) *(PIT_LDS f32x4_t*)(slot + i * 1024) = acc[4 * H + (i >> 3)][i & 7];
+  for (int i = 0; i < 4 * JA; ++i) *(PIT_LDS f32x4_t*)(slot + i * 1024) = acc[(JA / 2) * H + (i >> 3)][i & 7];
 }
-template <int H>
-__device__ __forceinline__ void red_recv_half(f32x4_t (&acc)[8][8], PIT_LDS char* slot) {
+template <int JA, int H>
+__device__ __forceinline__ void red_recv_half(f32x4_t (&acc)[JA][8], PIT_LDS char* slot) {
+  constexpr int CH = 4 * JA < 16 ? 4 * JA : 16;     // reads issued together, ahead of their additions
 #pragma unroll
-  for (int a = 0; a < 2; ++a) {
-    f32x4_t part[16];
+  for (int a = 0; a < 4 * JA / CH; ++a) {
+    f32x4_t part[CH];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) part[i] = *(PIT_LDS f32x4_t*)(slot + (a * 16 + i) * 1024);
+    for (int i = 0; i < CH; ++i) part[i] = *(PIT_LDS f32x4_t*)(slot + (a * CH + i) * 1024);
     PIT_SCHED_FENCE();
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[4 * H + 2 * a + (i >> 3)][i & 7] += part[i];
+    for (int i = 0; i < CH; ++i) acc[(JA / 2) * H + ((a * CH + i) >> 3)][(a * CH + i) & 7] += part[i];
     PIT_SCHED_FENCE();
   }
 }
-// Wave P stores its quarter of the tile: rows 32 * (lane / 16) + 8 e + ja; a lane holds 8
+// Store the row groups ja in [J0, J0 + NJ) of the tile: rows JA * (4 * (lane / 16) + e) + ja; a lane holds 8
 // consecutive columns of such a row (one per jb), so 16 lanes write 512 (fp32) or 256 contiguous bytes.
-template <bool BF, int CT, int P>
-__device__ __forceinline__ void red_store(const f32x4_t (&acc)[8][8], const GemmArgs& g, int m_base, int n0, int lane) {
+template <bool BF, int CT, int JA, int J0, int NJ>
+__device__ __forceinline__ void red_store(const f32x4_t (&acc)[JA][8], const GemmArgs& g, int m_base, int n0, int lane) {
   const int q = lane & 15, kb = lane >> 4;
 #pragma unroll
-  for (int a = 0; a < 2; ++a) {
-    const int ja = 2 * P + a;
+  for (int a = 0; a < NJ; ++a) {
+    const int ja = J0 + a;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int64_t row = m_base + 32 * kb + 8 * e + ja;
+      const int64_t row = m_base + JA * (4 * kb + e) + ja;
       const int col = n0 + 8 * q;
       if constexpr (CT == 0) {
         // (streaming stores: the result is not read again by this kernel and should not displace the
@@ -567,10 +594,17 @@ struct DirectTile {
 // workgroups, i.e. two tiles, share a compute unit at the same register cost, and the set-up, drain,
 // reduction and stores of one tile run under the MFMA loop of the other; used when there are at
 // least two tiles per compute unit).
-template <bool BF, int CT, int NW>
+// JA = row groups of the tile: the tile is 16 * JA rows high (128, 64 or 32 = the micro-tile height of the
+// index), a lane loads JA consecutive m of each listed row of At (16, 8 or 4 bytes) and a slab takes JA x 8
+// MFMAs.  Lower tiles follow a finer sparsity pattern (fewer all-zero micro-tiles are multiplied) and pay for
+// it with more traffic of B per row of C; they always run as two-wave workgroups, several per compute unit.
+template <bool BF, int CT, int NW, int JA>
 __global__ void __launch_bounds__(64 * NW)
 k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
+  static_assert(JA == 8 || (NW == 2 && (JA == 4 || JA == 2)), "tile heights: 128 (2 or 4 waves), 64 and 32 (2 waves)");
   constexpr int SK = 32;   // list entries per slab = k extent of one MFMA
+  constexpr int TMJ = 16 * JA;   // tile rows
+  constexpr int RED_HALF_BYTES = red_half_bytes<JA>();
   __shared__ __attribute__((aligned(16))) char s_red[NW == 4 ? 2 * RED_BUF_BYTES : 2 * RED_HALF_BYTES];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -600,7 +634,7 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     const int nslab = (t.list_len + SK - 1) / SK;
     t.n_w = nslab > wv ? (nslab - wv + NW - 1) / NW : 0;   // this wave's slabs: wv, wv + NW, ...
     t.list = uniform_ptr(g.idx + list_begin);
-    t.a_col = (uint32_t)(t.seg * TM + 8 * q) * 2u;
+    t.a_col = (uint32_t)(t.seg * TMJ + JA * q) * 2u;
     t.b_col = (uint32_t)(t.n0 + 8 * q) * 2u;
     return t;
   };
@@ -612,22 +646,22 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     return *(gint_t)(uintptr_t)(reinterpret_cast<uintptr_t>(T.list) + (uint32_t)pos * 4u);
   };
   // rows k(8 kb + i), i = 0..7, of At and of B
-  auto issue = [&](const DirectTile& T, int kraw, uint4 (&ra)[8], uint4 (&rb)[8]) {
+  auto issue = [&](const DirectTile& T, int kraw, ACols<JA> (&ra)[8], uint4 (&rb)[8]) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const uint32_t k = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * kb + i) * 4, kraw);
-      ra[i] = load16(a_src, __umul24(k, pitch_a) + T.a_col);
+      ra[i] = load_cols<JA>(a_src, __umul24(k, pitch_a) + T.a_col);
       rb[i] = load16(b_src, __umul24(k, pitch_b) + T.b_col);
     }
   };
 
-  f32x4_t acc[8][8];
+  f32x4_t acc[JA][8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < JA; ++i)
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  // 64 MFMAs on one slab.  All B operands are transposed first; the A operand of column group
+  // JA x 8 MFMAs on one slab (64 for the 128-row tile, which the description below is written for).  All B operands are transposed first; the A operand of column group
   // ja + 1 is transposed (4 v_perm_b32) in the shadow of the first MFMAs of group ja.  The order is
   // pinned: an MFMA must not read a register in the issue slot right after a vector instruction
   // wrote it, and the inline-assembly MFMAs are invisible to the compiler's hazard handling, so
@@ -636,15 +670,16 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
   // sequence as soon as their registers are free: the B rows during column groups 0..3 (rb is dead
   // once the B operands are transposed), the A rows during group 7 (ra is dead once the last A
   // operand is transposed).  Spreading them keeps 16 to 24 loads of a wave in flight; with 32 in
-  // flight at once the load path of a CU runs at less than half its rate (measured).
-  auto process_impl = [&](const DirectTile& T, uint4 (&ra)[8], uint4 (&rb)[8], int kraw, auto issue_tag) {
+  // flight at once the load path of a CU runs at less than half its rate (measured).  (Lower tiles: the B
+  // rows during the second half of every column group but the last, the A rows during the last group.)
+  auto process_impl = [&](const DirectTile& T, ACols<JA> (&ra)[8], uint4 (&rb)[8], int kraw, auto issue_tag) {
     constexpr bool ISSUE = decltype(issue_tag)::value;
     uint4 bfr[8];
 #pragma unroll
     for (int jb = 0; jb < 8; ++jb) bfr[jb] = transpose8x8_row(rb, jb);
     uint32_t af[4], afn[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) af[jj] = transpose8x8_dword(ra, 0, jj);
+    for (int jj = 0; jj < 4; ++jj) af[jj] = transpose_cols_dword<JA>(ra, 0, jj);
     uint32_t kk[8];
     if constexpr (ISSUE) {
 #pragma unroll
@@ -654,17 +689,26 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     asm volatile("s_nop 7");
     PIT_SCHED_FENCE();
 #pragma unroll
-    for (int ja = 0; ja < 8; ++ja) {
+    for (int ja = 0; ja < JA; ++ja) {
 #pragma unroll
       for (int jb = 0; jb < 8; ++jb) {
         mfma16_acc<BF>(make_uint4(af[0], af[1], af[2], af[3]), bfr[jb], acc[ja][jb]);
-        if (ja < 7 && jb < 4) afn[jb] = transpose8x8_dword(ra, ja + 1, jb);
+        if (ja < JA - 1 && jb < 4) afn[jb] = transpose_cols_dword<JA>(ra, ja + 1, jb);
         if constexpr (ISSUE) {
-          if (ja < 4 && (jb == 4 || jb == 6)) {
-            const int i = ja * 2 + ((jb - 4) >> 1);
-            rb[i] = load16(b_src, __umul24(kk[i], pitch_b) + T.b_col);
+          if constexpr (JA >= 4) {
+            if (ja < 4 && (jb == 4 || jb == 6)) {
+              const int i = ja * 2 + ((jb - 4) >> 1);
+              rb[i] = load16(b_src, __umul24(kk[i], pitch_b) + T.b_col);
+            }
+          } else {
+            if (jb >= 4) {   // JA == 2: 8 loads in the second halves of the two column groups
+              const int i = ja * 4 + (jb - 4);
+              rb[i] = load16(b_src, __umul24(kk[i], pitch_b) + T.b_col);
+            }
           }
-          if (ja == 7) ra[jb] = load16(a_src, __umul24(kk[jb], pitch_a) + T.a_col);
+          // (the A rows of the next-but-one slab may only replace ra once the last A operand of this
+          // slab has been taken out of it: during the last column group)
+          if (ja == JA - 1) ra[jb] = load_cols<JA>(a_src, __umul24(kk[jb], pitch_a) + T.a_col);
         }
         PIT_SCHED_FENCE();
       }
@@ -672,21 +716,26 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
       for (int jj = 0; jj < 4; ++jj) af[jj] = afn[jj];
     }
   };
-  auto process = [&](const DirectTile& T, uint4 (&ra)[8], uint4 (&rb)[8]) { process_impl(T, ra, rb, 0, std::false_type{}); };
-  auto process_issue = [&](const DirectTile& T, uint4 (&ra)[8], uint4 (&rb)[8], int kraw) { process_impl(T, ra, rb, kraw, std::true_type{}); };
+  auto process = [&](const DirectTile& T, ACols<JA> (&ra)[8], uint4 (&rb)[8]) { process_impl(T, ra, rb, 0, std::false_type{}); };
+  auto process_issue = [&](const DirectTile& T, ACols<JA> (&ra)[8], uint4 (&rb)[8], int kraw) { process_impl(T, ra, rb, kraw, std::true_type{}); };
   // local slab t with the rows of positions past the end of the list zeroed
-  auto process_last = [&](const DirectTile& T, int t, uint4 (&ra)[8], uint4 (&rb)[8]) {
+  auto process_last = [&](const DirectTile& T, int t, ACols<JA> (&ra)[8], uint4 (&rb)[8]) {
     const int p0 = SK * (wv + NW * t) + 8 * kb;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      if (p0 + i >= T.list_len) { ra[i] = make_uint4(0, 0, 0, 0); rb[i] = make_uint4(0, 0, 0, 0); }
+      if (p0 + i >= T.list_len) {
+#pragma unroll
+        for (int d = 0; d < JA / 2; ++d) ra[i].d[d] = 0u;
+        rb[i] = make_uint4(0, 0, 0, 0);
+      }
     process(T, ra, rb);
   };
 
   // With several tiles per workgroup the next tile's description and the list entries of its first
   // two slabs are fetched ahead of the current tile's reduction, so that only the row loads remain
   // between two tiles.
-  uint4 ra0[8], rb0[8], ra1[8], rb1[8];
+  ACols<JA> ra0[8], ra1[8];
+  uint4 rb0[8], rb1[8];
   PIT_LDS char* red = (PIT_LDS char*)s_red;
   int lin = blockIdx.x;
   DirectTile T = tile_of(lin);
@@ -722,37 +771,37 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     }
     PIT_SCHED_FENCE();
 
-    const int m_base = T.seg * TM;
+    const int m_base = T.seg * TMJ;
     if constexpr (NW == 4) {
       // Reduction across the four waves, one quarter of the tile rows per round, double-buffered in
       // LDS: round P's partial sums are written before barrier P and read by wave P after it, while the
       // other waves already write round P + 1 into the other buffer.
       if (wv != 0) red_send<0>(acc, red, wv, lane);
       __syncthreads();
-      if (wv == 0) { red_recv<0>(acc, red, lane); red_store<BF, CT, 0>(acc, g, m_base, T.n0, lane); }
+      if (wv == 0) { red_recv<0>(acc, red, lane); red_store<BF, CT, 8, 0, 2>(acc, g, m_base, T.n0, lane); }
       if (wv != 1) red_send<1>(acc, red + RED_BUF_BYTES, wv, lane);
       __syncthreads();
-      if (wv == 1) { red_recv<1>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 1>(acc, g, m_base, T.n0, lane); }
+      if (wv == 1) { red_recv<1>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 8, 2, 2>(acc, g, m_base, T.n0, lane); }
       if (wv != 2) red_send<2>(acc, red, wv, lane);
       __syncthreads();
-      if (wv == 2) { red_recv<2>(acc, red, lane); red_store<BF, CT, 2>(acc, g, m_base, T.n0, lane); }
+      if (wv == 2) { red_recv<2>(acc, red, lane); red_store<BF, CT, 8, 4, 2>(acc, g, m_base, T.n0, lane); }
       if (wv != 3) red_send<3>(acc, red + RED_BUF_BYTES, wv, lane);
       __syncthreads();
-      if (wv == 3) { red_recv<3>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 3>(acc, g, m_base, T.n0, lane); }
+      if (wv == 3) { red_recv<3>(acc, red + RED_BUF_BYTES, lane); red_store<BF, CT, 8, 6, 2>(acc, g, m_base, T.n0, lane); }
     } else {
       // The two waves trade the halves of their partial tiles that the other one owns (wave 0: the
       // row groups ja < 4).  The first barrier keeps a wave from overwriting what the other still
       // reads for the previous tile.
       __syncthreads();
-      if (wv == 0) red_send_half<1>(acc, red + lane * 16);
-      else         red_send_half<0>(acc, red + RED_HALF_BYTES + lane * 16);
+      if (wv == 0) red_send_half<JA, 1>(acc, red + lane * 16);
+      else         red_send_half<JA, 0>(acc, red + RED_HALF_BYTES + lane * 16);
       __syncthreads();
       if (wv == 0) {
-        red_recv_half<0>(acc, red + RED_HALF_BYTES + lane * 16);
-        red_store<BF, CT, 0>(acc, g, m_base, T.n0, lane); red_store<BF, CT, 1>(acc, g, m_base, T.n0, lane);
+        red_recv_half<JA, 0>(acc, red + RED_HALF_BYTES + lane * 16);
+        red_store<BF, CT, JA, 0, JA / 2>(acc, g, m_base, T.n0, lane);
       } else {
-        red_recv_half<1>(acc, red + lane * 16);
-        red_store<BF, CT, 2>(acc, g, m_base, T.n0, lane); red_store<BF, CT, 3>(acc, g, m_base, T.n0, lane);
+        red_recv_half<JA, 1>(acc, red + lane * 16);
+        red_store<BF, CT, JA, JA / 2, JA / 2>(acc, g, m_base, T.n0, lane);
       }
     }
     if (!more) break;
@@ -760,7 +809,7 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     lin = lin_next;
     T = Tn;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < JA; ++i)
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
@@ -1086,11 +1135,18 @@ static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
     static_assert(EPI == EPI_STORE, "GATHER_K has the plain store epilogue only");
     // one workgroup fits on a compute unit: with more tiles than compute units the workgroups loop
     const int total = (int)(grid.x * grid.y), cus = compute_units();
-    if (total >= 2 * cus) {      // two workgroups of two waves per compute unit
-      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2>), dim3((unsigned)(2 * cus)), dim3(128), 0, st, g, (int)grid.y);
+    if (g.slab == 64 || g.slab == 32) {
+      // lower tiles: two-wave workgroups; as many as the registers let a compute unit hold (64 rows: two,
+      // 32 rows: four, i.e. two waves per SIMD)
+      const int resident = (g.slab == 64 ? 2 : 4) * cus;
+      const unsigned wgs = (unsigned)(total <= resident ? total : resident);
+      if (g.slab == 64) hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 4>), dim3(wgs), dim3(128), 0, st, g, (int)grid.y);
+      else              hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 2>), dim3(wgs), dim3(128), 0, st, g, (int)grid.y);
+    } else if (total >= 2 * cus) {      // two workgroups of two waves per compute unit
+      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 8>), dim3((unsigned)(2 * cus)), dim3(128), 0, st, g, (int)grid.y);
     } else {
       const unsigned wgs = (unsigned)(total <= cus ? total : cus);
-      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 4>), dim3(wgs), dim3(256), 0, st, g, (int)grid.y);
+      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 4, 8>), dim3(wgs), dim3(256), 0, st, g, (int)grid.y);
     }
     PIT_LAUNCH_CHECK();
     return PIT_OK;
@@ -1161,10 +1217,10 @@ extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void
   g.nseg = ix->nseg; g.M = M; g.N = N; g.K = K;
 
   if (mode == PIT_GEMM_GATHER_K) {
-    if (mt != TM || M % TM) return PIT_ESHAPE;
-    if (ix->nseg != M / TM) return PIT_ECAPACITY;
+    if ((mt != 128 && mt != 64 && mt != 32) || M % mt) return PIT_ESHAPE;
+    if (ix->nseg != M / mt) return PIT_ECAPACITY;
     if (K > 0 && lda < M) return PIT_EINVAL;
-    g.slab = 0;
+    g.slab = mt;       // GATHER_K: the tile height (= micro-tile height of the index)
     return launch_sread_gemm(in_dt == PIT_BF16, true, EPI_STORE, c_dt != PIT_F32, g, ix->nseg, st);
   }
 

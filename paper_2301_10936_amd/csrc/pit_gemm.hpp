@@ -47,6 +47,7 @@ struct GemmArgs {
   const float* gate;                                   // per C row (EPI_STORE with scatter), or nullptr
   int nseg, M, N, K;
   int slab;          // GATHER_M: k extent of one segment's slab (K when nseg == 1 or per-segment weights)
+                     // GATHER_K: rows of a tile = micro-tile height of the index (128, 64 or 32)
   int a_gather;      // GATHER_M: 1 = A rows come from idx, 0 = A rows are seg_ptr[s] + r (compact)
   int c_scatter;     // GATHER_M: 1 = C rows go to idx, 0 = C rows are seg_ptr[s] + r (compact)
   int slab_per_seg;  // GATHER_M: 1 = segment s covers k in [s*slab, (s+1)*slab), 0 = every segment covers [0, K)

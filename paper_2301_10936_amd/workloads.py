@@ -87,12 +87,15 @@ class ReluFfn:
 
 
 def relu_ffn(M=2048, K=8192, N=2048, mean=-1.2, w_std=0.02, seed=None, call=0, integer=False,
-             channel_live_prob: float | None = None) -> ReluFfn:
+             channel_live_prob: float | None = None, live_block: int = 128, live_offset: int = 0) -> ReluFfn:
     """X = ReLU(N(mean, 1)) stored channel-major, W ~ N(0, w_std).
 
     ``channel_live_prob`` (optional) adds zeros that are correlated across tokens: a channel is
-    silenced for a whole block of 128 tokens with probability 1 - channel_live_prob, which is the
-    regime where whole micro-tiles vanish.  The default (None) is the independent-zeros recipe.
+    silenced for a whole run of ``live_block`` consecutive tokens with probability
+    1 - channel_live_prob, which is the regime where whole micro-tiles vanish.  The runs start at
+    tokens ``live_offset + i * live_block`` (the tokens before ``live_offset`` form a shorter first
+    run), so with ``live_offset`` = 64 a run of 128 straddles two aligned blocks of 128 tokens.
+    The default (None) is the independent-zeros recipe.
     """
     g = rng_for(2, call, seed)
     if integer:
@@ -103,10 +106,11 @@ def relu_ffn(M=2048, K=8192, N=2048, mean=-1.2, w_std=0.02, seed=None, call=0, i
         W = g.standard_normal((K, N), dtype=np.float32) * np.float32(w_std)
     X = np.maximum(X, np.float32(0.0))
     if channel_live_prob is not None:
-        blk = 128
-        nb = (M + blk - 1) // blk
+        blk = int(live_block)
+        lead = (blk - int(live_offset) % blk) % blk          # tokens dropped from the front of the first run
+        nb = (M + lead + blk - 1) // blk
         live = g.random((K, nb)) < channel_live_prob
-        live = np.repeat(live, blk, axis=1)[:, :M]
+        live = np.repeat(live, blk, axis=1)[:, lead:lead + M]
         X = X * live
     return ReluFfn(Xt=to_bf16_bits(X), W=to_bf16_bits(W), M=M, K=K, N=N)
 

@@ -60,7 +60,7 @@ def test_single_key_per_query_copies_value_rows(pit):
     m[np.arange(96), tgt] = 1
     O = _run(pit, w, mask=m).cpu().numpy()
     V = orc.to_f64(w.V)
-    assert np.allclose(O, V[:, tgt], rtol=2.0 ** -10, atol=0)     # P = 1 exactly; V passes through fp16
+    assert np.array_equal(O, V[:, tgt])     # P = 1 exactly and bf16 V enters the product unchanged
 
 
 def test_all_masked_gives_zeros(pit):
@@ -97,3 +97,27 @@ def test_attn_error_returns(pit):
         _run(pit, w)
     assert e.value.code == pit.PIT_ESHAPE
     assert pit.pit_sparse_attn_workspace(1, 40, 64) == 0
+
+
+def test_values_far_outside_the_fp16_range(pit):
+    """bf16 V rows of magnitude 1e5 (beyond fp16's largest finite value) and 1e-9 (below its smallest
+    subnormal) must come through: V enters the second product as bf16, not through a narrower type."""
+    w = wl.sparse_attn(H=3, S=256, window=32, density=0.1, seed=21)
+    V = orc.bf16_bits_to_f64(w.V)
+    V[0] *= 1e5
+    V[1] *= 1e-9
+    V[2, ::2] *= 1e5          # both magnitudes among the keys of one query
+    V[2, 1::2] *= 1e-9
+    w.V = wl.to_bf16_bits(V.astype(np.float32))
+    O = _run(pit, w, sentinel=3.0)
+    assert bool(torch.isfinite(O).all())
+    ref = orc.sparse_attn(w.Q, w.K, w.V, w.mask, w.scale)
+    assert float(np.abs(ref[0]).max()) > 65504.0 and 0.0 < float(np.abs(ref[1]).max()) < 2.0 ** -24
+    for h in range(3):
+        assert_close(O[h], ref[h], f"head {h}")
+    # a query that sees only tiny values: single-key mask over the 1e-9 rows of head 2 copies them exactly
+    m = np.zeros((256, 256), dtype=np.uint8)
+    m[np.arange(256), 1] = 1
+    O1 = _run(pit, w, mask=m).cpu().numpy()
+    Vq = orc.to_f64(w.V)
+    assert np.array_equal(O1[2], np.broadcast_to(Vq[2, 1], (256, 64))) and np.all(O1[2, 0] != 0)

@@ -17,28 +17,50 @@ def pit():
 
 
 # ------------------------------------------------------------------ GATHER_K (k is the PIT-axis)
-def _run_gather_k(pit, w, c_dtype=torch.float32):
+MTS = [128, 64, 32]     # tile heights of the GATHER_K kernel = micro-tile heights of its index
+
+
+def _run_gather_k(pit, w, c_dtype=torch.float32, mt=128, sentinel=None):
     Xt, W = to_dev(w.Xt), to_dev(w.W)
-    ix = pit.pit_build_index(Xt, 1, 128, 0)
-    C = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, 128, w.M, w.N, w.K, c_dtype=c_dtype)
+    ix = pit.pit_build_index(Xt, 1, mt, 0)
+    out = None if sentinel is None else torch.full((w.M, w.N), sentinel, dtype=c_dtype, device=dev())
+    C = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, mt, w.M, w.N, w.K, c_dtype=c_dtype, out=out)
     torch.cuda.synchronize()
-    assert_index_equal(ix, orc.build_index(w.Xt, 1, 128, 0))
+    assert_index_equal(ix, orc.build_index(w.Xt, 1, mt, 0))
     return C
 
 
+@pytest.mark.parametrize("mt", MTS)
 @pytest.mark.parametrize("M,K,N", [(128, 64, 128), (256, 200, 128), (384, 1000, 256), (128, 8, 384)])
-def test_gather_k_exact_on_integers(pit, M, K, N):
+def test_gather_k_exact_on_integers(pit, M, K, N, mt):
     """Small-integer data: every partial sum is exact in fp32, so the result must match bit for bit."""
     w = wl.relu_ffn(M=M, K=K, N=N, seed=M + K, integer=True)
-    C = _run_gather_k(pit, w)
+    C = _run_gather_k(pit, w, mt=mt, sentinel=77.0)
     assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(w.Xt, w.W))
 
 
+@pytest.mark.parametrize("mt", MTS)
 @pytest.mark.parametrize("prob", [None, 0.25, 0.02])
-def test_gather_k_float(pit, prob):
+def test_gather_k_float(pit, prob, mt):
     w = wl.relu_ffn(M=512, K=1536, N=384, seed=3, channel_live_prob=prob)
-    C = _run_gather_k(pit, w)
+    C = _run_gather_k(pit, w, mt=mt)
     assert_close(C, orc.gemm_at(w.Xt, w.W), "gather_k")
+
+
+@pytest.mark.parametrize("mt", MTS)
+@pytest.mark.parametrize("block,offset", [(32, 0), (128, 64), (64, 32), (96, 16)])
+def test_gather_k_dead_runs_not_aligned_to_the_tile(pit, block, offset, mt):
+    """Channels silent for runs of `block` tokens starting at `offset`: runs shorter than the 128-row tile, and
+    runs of the tile's length that straddle two tiles.  The lists of neighbouring segments then differ in
+    other ways than in the recipe whose runs coincide with the tiles; exact on integers."""
+    w = wl.relu_ffn(M=640, K=700, N=256, seed=block + offset, integer=True, channel_live_prob=0.3,
+                    live_block=block, live_offset=offset)
+    C = _run_gather_k(pit, w, mt=mt, sentinel=-5.0)
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(w.Xt, w.W))
+    # the finer index lists no more micro-tile area than the coarser one, and strictly less when runs are short
+    n128 = int(orc.build_index(w.Xt, 1, 128, 0)[0][-1]) * 128
+    nmt = int(orc.build_index(w.Xt, 1, mt, 0)[0][-1]) * mt
+    assert nmt <= n128 and (mt == 128 or block >= 128 and offset == 0 or nmt < n128)
 
 
 def test_gather_k_all_zero_and_sentinel(pit):
@@ -52,15 +74,16 @@ def test_gather_k_all_zero_and_sentinel(pit):
     assert int(ix.seg_ptr[-1]) == 0 and torch.count_nonzero(C) == 0
 
 
-def test_gather_k_fp16_and_rounded_output(pit):
+@pytest.mark.parametrize("mt", MTS)
+def test_gather_k_fp16_and_rounded_output(pit, mt):
     g = np.random.default_rng(6)
     At = (np.maximum(g.standard_normal((300, 256)) - 1.0, 0)).astype(np.float16)
     B = (g.standard_normal((300, 256)) * 0.05).astype(np.float16)
     tA, tB = to_dev(At), to_dev(B)
-    ix = pit.pit_build_index(tA, 1, 128, 0)
+    ix = pit.pit_build_index(tA, 1, mt, 0)
     ref = orc.gemm_at(At, B)
-    C = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, tB, ix, 128, 256, 256, 300)
-    Ch = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, tB, ix, 128, 256, 256, 300, c_dtype=torch.float16)
+    C = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, tB, ix, mt, 256, 256, 300)
+    Ch = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, tB, ix, mt, 256, 256, 300, c_dtype=torch.float16)
     torch.cuda.synchronize()
     assert_close(C, ref, "fp16 in, fp32 out")
     # rounded store: one rounding of the fp32 accumulator, so within 1 fp16 ulp of the rounded oracle
@@ -70,9 +93,10 @@ def test_gather_k_fp16_and_rounded_output(pit):
     assert np.all(np.abs(got.astype(np.float64) - want.astype(np.float64)) <= ulp + 1e-6 * np.abs(ref))
 
 
-def test_gather_k_bf16_output(pit):
+@pytest.mark.parametrize("mt", MTS)
+def test_gather_k_bf16_output(pit, mt):
     w = wl.relu_ffn(M=256, K=512, N=256, seed=8)
-    C = _run_gather_k(pit, w, c_dtype=torch.bfloat16)
+    C = _run_gather_k(pit, w, c_dtype=torch.bfloat16, mt=mt)
     ref = orc.gemm_at(w.Xt, w.W)
     got = orc.bf16_bits_to_f64(bf16_bits(C))
     want = orc.round_to_bf16(ref)
@@ -81,8 +105,9 @@ def test_gather_k_bf16_output(pit):
     assert fro < 3e-3   # bf16 storage alone costs ~1.7e-3; reported, the fp32 path carries the 1e-3 gate
 
 
+@pytest.mark.parametrize("mt", MTS)
 @pytest.mark.parametrize("live", [1, 2, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 160, 161, 255, 257])
-def test_gather_k_list_lengths_around_slab_boundaries(pit, live):
+def test_gather_k_list_lengths_around_slab_boundaries(pit, live, mt):
     """The four waves split the k-list in slabs of 32: lengths that leave waves without work, with
     one slab, with a partial last slab, with an odd and an even number of slabs."""
     g = np.random.default_rng(1000 + live)
@@ -97,15 +122,16 @@ def test_gather_k_list_lengths_around_slab_boundaries(pit, live):
     W = g.integers(-3, 4, size=(K, N)).astype(np.float32)
     xb, wb = wl.to_bf16_bits(Xt), wl.to_bf16_bits(W)
     tX, tW = to_dev(xb), to_dev(wb)
-    ix = pit.pit_build_index(tX, 1, 128, 0)
-    C = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K)
+    ix = pit.pit_build_index(tX, 1, mt, 0)
+    C = pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, mt, M, N, K)
     torch.cuda.synchronize()
-    assert_index_equal(ix, orc.build_index(xb, 1, 128, 0))
+    assert_index_equal(ix, orc.build_index(xb, 1, mt, 0))
     assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(xb, wb))
 
 
+@pytest.mark.parametrize("mt", MTS)
 @pytest.mark.parametrize("tiles_m,tiles_n", [(24, 12), (9, 57), (65, 8)])
-def test_gather_k_more_tiles_than_compute_units(pit, tiles_m, tiles_n):
+def test_gather_k_more_tiles_than_compute_units(pit, tiles_m, tiles_n, mt):
     """More 128 x 128 tiles than the GPU has compute units: workgroups loop over tiles (accumulators
     and reduction buffers are reused from tile to tile).  Segment lengths differ from tile row
     to tile row (empty, shorter than one slab, waves without work, many slabs), so consecutive
@@ -124,19 +150,20 @@ def test_gather_k_more_tiles_than_compute_units(pit, tiles_m, tiles_n):
     W = g.integers(-3, 4, size=(K, N)).astype(np.float32)
     xb, wb = wl.to_bf16_bits(Xt), wl.to_bf16_bits(W)
     tX, tW = to_dev(xb), to_dev(wb)
-    ix = pit.pit_build_index(tX, 1, 128, 0)
+    ix = pit.pit_build_index(tX, 1, mt, 0)
     C = torch.full((M, N), 7.0, device=dev())
-    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K, out=C)
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, mt, M, N, K, out=C)
     torch.cuda.synchronize()
-    assert_index_equal(ix, orc.build_index(xb, 1, 128, 0))
+    assert_index_equal(ix, orc.build_index(xb, 1, mt, 0))
     assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(xb, wb))
     # twice in a row on the same output: nothing of the first call may leak into the second
-    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K, out=C)
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, mt, M, N, K, out=C)
     torch.cuda.synchronize()
     assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(xb, wb))
 
 
-def test_gather_k_strided_operands_and_large_last_row(pit):
+@pytest.mark.parametrize("mt", MTS)
+def test_gather_k_strided_operands_and_large_last_row(pit, mt):
     """Row pitches larger than the row length (views into wider buffers); the last listed row holds
     the largest finite bf16 values: positions past the end of the list re-read that row and must
     contribute nothing (and no Inf - Inf)."""
@@ -153,8 +180,8 @@ def test_gather_k_strided_operands_and_large_last_row(pit):
     bigW[:, :N] = to_dev(wb)
     tX, tW = bigX[:, :M], bigW[:, :N]
     outbuf = torch.full((M, N + 32), 9.0, device=dev())
-    ix = pit.pit_build_index(tX, 1, 128, 0)
-    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, 128, M, N, K, out=outbuf[:, :N])
+    ix = pit.pit_build_index(tX, 1, mt, 0)
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tX, tW, ix, mt, M, N, K, out=outbuf[:, :N])
     torch.cuda.synchronize()
     ref = orc.gemm_at(xb, wb)
     got = outbuf[:, :N].cpu().numpy().astype(np.float64)
@@ -163,9 +190,12 @@ def test_gather_k_strided_operands_and_large_last_row(pit):
     assert torch.all(outbuf[:, N:] == 9.0)     # nothing written outside the N columns
 
 
-def test_c2_full_size(pit):
+@pytest.mark.parametrize("mt", MTS)
+def test_c2_full_size(pit, mt):
+    """The headline shape at the tile height the bench times (128) and at the 32 x 1 micro-tile its
+    workload is stated in (and 64)."""
     w = wl.relu_ffn()
-    C = _run_gather_k(pit, w)
+    C = _run_gather_k(pit, w, mt=mt)
     assert_close(C, orc.gemm_at(w.Xt, w.W), "C2 full size")
 
 
@@ -332,8 +362,11 @@ def test_gemm_error_returns(pit):
     Xt, W = to_dev(w.Xt), to_dev(w.W)
     ix = pit.pit_build_index(Xt, 1, 128, 0)
     with pytest.raises(pit.PitError) as e:
-        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, 64, 128, 128, 64)
+        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, 16, 128, 128, 64)       # tile heights are 32, 64, 128
     assert e.value.code == pit.PIT_ESHAPE
+    with pytest.raises(pit.PitError) as e:
+        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, 64, 128, 128, 64)       # index built at 128, not at 64
+    assert e.value.code == pit.PIT_ECAPACITY
     with pytest.raises(pit.PitError) as e:
         pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W[:, :100], ix, 128, 128, 100, 64)
     assert e.value.code == pit.PIT_ESHAPE

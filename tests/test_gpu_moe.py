@@ -83,19 +83,16 @@ def test_empty_batch(pit):
     assert Y.shape == (0, 128)
 
 
-def test_c3_full_size_sampled_tokens(pit):
-    """Full Switch-style shape; the per-token oracle is evaluated on a sample of tokens that
-    includes every expert's first and last token (tile edges)."""
+def test_c3_full_size_every_token(pit):
+    """Full Switch-style shape (4096 tokens, 64 experts, Zipf routing: experts with 7 to ~1000 tokens, 80 row
+    tiles).  Every one of the 4096 output rows is compared with the per-token oracle, so a gather or scatter
+    mistake on any token, at any tile edge, fails."""
     w = wl.moe_ffn()
     Y, st = _run(pit, w, sentinel=11.0)
     assert st == 0
-    g = np.random.default_rng(0)
-    sel = set(g.choice(4096, 384, replace=False).tolist())
-    for e in range(64):
-        toks = np.flatnonzero(w.expert_id == e)
-        if len(toks):
-            sel.update([int(toks[0]), int(toks[-1])])
-    sel = np.array(sorted(sel))
-    ref = orc.moe_ffn(w.X[sel], w.expert_id[sel], w.gate[sel], w.W1, w.W2)
-    assert_close(Y[to_dev(sel)], ref, "C3 sampled")
-    assert bool(torch.isfinite(Y).all()) and float(Y.abs().max()) < 11.0
+    ref = orc.moe_ffn(w.X, w.expert_id, w.gate, w.W1, w.W2)
+    assert_close(Y, ref, "C3 all tokens")
+    # per token as well: a single wrong row would hardly move the Frobenius norm of 4096 rows
+    got = Y.cpu().numpy().astype(np.float64)
+    row_err = np.linalg.norm(got - ref, axis=1) / np.maximum(np.linalg.norm(ref, axis=1), 1e-30)
+    assert float(row_err.max()) <= 4e-3, (int(row_err.argmax()), float(row_err.max()))
