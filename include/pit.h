@@ -95,6 +95,24 @@ int pit_build_index(const void* d_src, int dt, int rows, int cols, int64_t ld,
                     int mt_rows, int mt_cols, int pit_dim,
                     const pit_index* out, void* d_ws, size_t ws_bytes, pit_stream stream);
 
+/*
+ * pit_build_index for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * pit_build_index, without d_ws / ws_bytes: the workspace is a fixed device array inside the
+ * library (pit_build_index_static_capacity() bytes, 1 MiB, held by every GPU the library has run
+ * on until the process ends).  The call allocates nothing and frees nothing.
+ *   PIT_ECAPACITY  if pit_build_index_workspace(...) for this problem exceeds the capacity
+ *                  (e.g. a 4096 x 4096 byte mask at 1 x 1); nothing is enqueued then.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (other
+ * streams, other threads) race on it and must be serialised by the caller; calls enqueued on one
+ * stream are ordered and safe.  The array keeps the previous call's contents; the build either
+ * overwrites or clears every word it reads, so no clearing is needed between calls.
+ */
+size_t pit_build_index_static_capacity(void);
+int pit_build_index_static(const void* d_src, int dt, int rows, int cols, int64_t ld,
+                           int mt_rows, int mt_cols, int pit_dim,
+                           const pit_index* out, pit_stream stream);
+
 /* Bytes of device workspace pit_build_route_index needs. */
 size_t pit_build_route_index_workspace(int T, int E);
 

@@ -1058,3 +1058,60 @@ extern "C" int pit_build_route_index(const int32_t* d_expert_id, int T, int E, c
   PIT_LAUNCH_CHECK();
   return launch_emit(L, words, cnt, nullptr, out, T, d_status, st);
 }
+
+// ----------------------------------------------------------------------------------------------
+// pit_build_index for callers that cannot allocate: the workspace (bitmap words, occupancy words,
+// per-segment counts) lives in a file-scope device array instead of a caller's buffer.  Each GPU
+// holds its own copy of the array at its own address; host code never uses the array's name as a
+// pointer, only the address hipGetSymbolAddress reports for the current device.
+// ----------------------------------------------------------------------------------------------
+namespace pit {
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+}  // namespace
+}  // namespace pit
+static __device__ __align__(256) unsigned char scratch[pit::kStaticScratchBytes];
+
+#include <mutex>
+namespace pit {
+namespace {
+// device address of `scratch` on the current device, looked up once per device
+int static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  PIT_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return PIT_EINVAL;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    PIT_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return PIT_EINVAL;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return PIT_OK;
+}
+}  // namespace
+}  // namespace pit
+
+extern "C" size_t pit_build_index_static_capacity(void) { return pit::kStaticScratchBytes; }
+
+extern "C" int pit_build_index_static(const void* d_src, int dt, int rows, int cols, int64_t ld,
+                                      int mt_rows, int mt_cols, int pit_dim,
+                                      const pit_index* out, pit_stream stream) {
+  // argument errors are reported exactly as by pit_build_index, before the scratch array is touched
+  const int esize = dtype_size(dt);
+  if (!out || !out->seg_ptr || esize == 0 || (pit_dim != 0 && pit_dim != 1)) return PIT_EINVAL;
+  if (rows < 0 || cols < 0 || mt_rows <= 0 || mt_cols <= 0) return PIT_ESHAPE;
+  if (rows % mt_rows || cols % mt_cols) return PIT_ESHAPE;
+  const size_t need = pit_build_index_workspace(rows, cols, mt_rows, mt_cols, pit_dim, out->bits != nullptr);
+  if (need > kStaticScratchBytes) return PIT_ECAPACITY;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != PIT_OK) return rc;
+  // (every path of pit_build_index either writes each workspace word it later reads or clears it
+  // with a fill kernel first, so what the previous call left in the array does not matter)
+  return pit_build_index(d_src, dt, rows, cols, ld, mt_rows, mt_cols, pit_dim, out, ws, kStaticScratchBytes, stream);
+}

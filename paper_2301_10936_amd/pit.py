@@ -24,6 +24,7 @@ PIT_GEMM_GATHER_M, PIT_GEMM_GATHER_K = 0, 1
 _STATUS = {0: "PIT_OK", -1: "PIT_EINVAL", -2: "PIT_ESHAPE", -3: "PIT_ECAPACITY", -4: "PIT_EHIP"}
 
 EXPORTS = ["pit_last_hip_error", "pit_version", "pit_build_index_workspace", "pit_build_index",
+           "pit_build_index_static_capacity", "pit_build_index_static",
            "pit_build_route_index_workspace", "pit_build_route_index",
            "pit_relu_channel_major_index_workspace", "pit_relu_channel_major_index",
            "pit_cover_count_workspace", "pit_cover_count", "pit_select_kernel", "pit_sread_gemm",
@@ -43,6 +44,10 @@ _lib.pit_build_index_workspace.restype = c_sz
 _lib.pit_build_index_workspace.argtypes = [c_int] * 6
 _lib.pit_build_index.restype = c_int
 _lib.pit_build_index.argtypes = [c_vp, c_int, c_int, c_int, c_i64, c_int, c_int, c_int, _P, c_vp, c_sz, c_vp]
+_lib.pit_build_index_static_capacity.restype = c_sz
+_lib.pit_build_index_static_capacity.argtypes = []
+_lib.pit_build_index_static.restype = c_int
+_lib.pit_build_index_static.argtypes = [c_vp, c_int, c_int, c_int, c_i64, c_int, c_int, c_int, _P, c_vp]
 _lib.pit_build_route_index_workspace.restype = c_sz
 _lib.pit_build_route_index_workspace.argtypes = [c_int, c_int]
 _lib.pit_build_route_index.restype = c_int
@@ -155,6 +160,21 @@ def pit_build_index(src: torch.Tensor, mt_rows: int, mt_cols: int, pit_dim: int,
     _check(_lib.pit_build_index(src.data_ptr(), _dt(src), rows, cols, src.stride(0) if rows > 1 else max(cols, src.stride(0)),
                                 mt_rows, mt_cols, pit_dim, ctypes.byref(ci), ws.data_ptr(), ws.numel(), _stream()),
            "pit_build_index")
+    return out
+
+
+def pit_build_index_static_capacity() -> int:
+    return _lib.pit_build_index_static_capacity()
+
+
+def pit_build_index_static(src: torch.Tensor, mt_rows: int, mt_cols: int, pit_dim: int, out: PitIndex) -> PitIndex:
+    """pit_build_index with the workspace inside the library (no allocation anywhere on the way: `out` is
+    the caller's).  See include/pit.h."""
+    assert src.dim() == 2 and src.stride(1) == 1
+    rows, cols = src.shape
+    ci = out.c()
+    _check(_lib.pit_build_index_static(src.data_ptr(), _dt(src), rows, cols, src.stride(0) if rows > 1 else max(cols, src.stride(0)),
+                                       mt_rows, mt_cols, pit_dim, ctypes.byref(ci), _stream()), "pit_build_index_static")
     return out
 
 
