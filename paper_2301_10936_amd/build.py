@@ -12,8 +12,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpit_hip.so")
-SOURCES = ["pit_api.hip", "pit_index.hip", "pit_gemm.hip", "pit_moe.hip", "pit_attn.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+SOURCES = ["pit_api.hip", "pit_index.hip", "pit_gemm.hip", "pit_gemm_m.hip", "pit_moe.hip", "pit_attn.hip"]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wno-inline-asm", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

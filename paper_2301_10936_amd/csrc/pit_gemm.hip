@@ -1,466 +1,25 @@
 // pit_sread_gemm: the SRead -> dense MFMA tile -> SWrite kernels (paper Section 3.1, sparse kernel
-// template) for gfx950, and their host-side validation and launch.
-//
-// A workgroup (256 threads = 4 wavefronts) computes a 128 x 128 dense tile of C with bf16 or f16
-// inputs and fp32 accumulation.  There is one kernel per PIT-axis of MatMul (paper Table 1):
+// template) for gfx950 with k as the PIT-axis, or m with micro-tiles along k, and the host-side
+// validation and launch of all GEMM modes.  bf16 or f16 inputs, fp32 accumulation.
+// There is one kernel per PIT-axis of MatMul (paper Table 1):
 //
 //   k_gather_k_direct  GATHER_K: A is K-major (At[k][m]); the tile's k-list comes from the index and
 //             names the rows of At and of B to multiply.  Operands go global -> registers directly
-//             and are transposed inside each lane; the four waves split the k-list and reduce
-//             their partial tiles through LDS at the end (details above the kernel).
-//   k_gather_m  GATHER_M: A is K-minor (A[m][k]); the tile's 128 row numbers come from the index
-//             once, the k loop walks a contiguous k range; B rows are contiguous.  Operands are
-//             staged through LDS, 2 x 2 waves of 64 x 64 with v_mfma_f32_32x32x16, 64 k per step.
+//             and are transposed inside each lane; the waves of a workgroup split the k-list and
+//             reduce their partial tiles through LDS at the end (details above the kernel).
+//             Tiles of 128, 64 or 32 rows x 128 columns.
+//   k_slab_strip  GATHER_M with several k-slabs per row (1 x mt micro-tiles of a row-major A): a strip
+//             of C stays in LDS while the listed rows of every slab are added to it.
+//   k_gather_m_lds (pit_gemm_m.hip)  GATHER_M with whole-row micro-tiles (padded batches, MoE): the
+//             tile's row numbers come from the index once, operands are staged through LDS.
 //
-// k_gather_m in detail.  Both operand tiles are K-MINOR in LDS ([128 x][64 k], 128 B per row) and
-// are read with ds_read_b128.  The K-major source (rows of B) is transposed in registers on the way
-// in: a thread loads an 8 k x 8 column block (8 x 16 B, one source row each), interleaves the 16-bit
-// elements with v_perm_b32 and writes 8 tile rows of 16 B.  Global loads run 2 steps ahead in a
-// register ring.  The steady-state loop is branch-free: all loads are unconditional (k past the end
-// of the slab is clamped and zeroed on the way into LDS, in the last step only).  Inside a step the
-// LDS reads of k-substep s+1, the transposes and the LDS writes of the next tile are interleaved
-// with the MFMAs of k-substep s, so the LDS pipe and the matrix pipe work at the same time although
-// there is a single wavefront per SIMD.
-//
-// SWrite.  The GATHER_M epilogue stores accumulator rows to the row numbers held in LDS (compact or
-// from the index), optionally with a GELU + round to the input type (first MoE matmul) or a per-row
-// gate (second MoE matmul).  GATHER_K writes the rows of its m-tile in place.  Several k-slabs per
-// row (micro-tiles along k) have a kernel of their own, k_slab_strip, which keeps C in LDS.
+// SWrite.  GATHER_K writes the rows of its m-tile in place; k_slab_strip stores whole strips.
 #include "pit_gemm.hpp"
+#include "pit_gemm_dev.hpp"
 #include <type_traits>
 
 namespace pit {
 namespace {
-
-__device__ __forceinline__ void lds_write_b128(uint32_t addr, const uint4& v) {
-  *(PIT_LDS u32x4_t*)(uintptr_t)addr = __builtin_bit_cast(u32x4_t, v);
-}
-__device__ __forceinline__ u32x4_t lds_read_frag(uint32_t addr) {
-  return *(PIT_LDS u32x4_t*)(uintptr_t)addr;
-}
-template <bool BF>
-__device__ __forceinline__ f32x16_t mfma32(const u32x4_t& a, const u32x4_t& b, const f32x16_t& c) {
-  if constexpr (BF)
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-  else
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ uint16_t f32_to_f16_rne(float f) {
-  return __builtin_bit_cast(uint16_t, (_Float16)f);
-}
-template <bool BF> __device__ __forceinline__ uint16_t f32_to_in(float f) {
-  return BF ? f32_to_bf16_rne(f) : f32_to_f16_rne(f);
-}
-// GELU(x) = x (1 + erf(x / sqrt 2)) / 2 with erf from the rational approximation 7.1.26 of Abramowitz & Stegun
-// (|error| <= 1.5e-7, far below the rounding of the result to bf16 / fp16): a fifth of the
-// instructions of erff; the GELU epilogue of the first MoE matmul is a quarter of its workgroups' run time otherwise.
-__device__ __forceinline__ float gelu_erf_fast(float x) {
-  const float z = fabsf(x) * 0.70710678118654752f;
-  const float t = __frcp_rn(1.0f + 0.3275911f * z);
-  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  const float e = 1.0f - poly * __expf(-z * z);          // erf(|x| / sqrt 2)
-  return 0.5f * x * (1.0f + copysignf(e, x));
-}
-
-// Global loads are laid out so that 16 consecutive lanes read 256 contiguous bytes of one source
-// row (the address unit merges 4 neighbouring lanes into one 64-byte request; lanes that jump
-// between rows cost one request each, four times the address-unit time).
-//
-// LDS address of 16-byte chunk c (8 k) of tile row m, with a = m >> 4, h = (m >> 3) & 1, l = m & 7:
-//   256-byte bank row = a * 8 + l,   128-byte half = h,   16-byte slot inside the half = c ^ l ^ a
-// The LDS serves 16 lanes per clock and conflicts are decided by the position inside the
-// 256-byte bank row.  All three access shapes put 16 lanes on 16 different positions:
-//   operand read        16 consecutive rows (a fixed; h, l vary), one chunk
-//   transposing write   rows 8*cg + x for 16 consecutive cg (l = x fixed; a, h vary), one chunk
-//   straight write      rows m and m + 8 (h differs), all 8 chunks each
-// (measured: XOR rotations keep ds_read_b128 at its full rate, additive rotations cost ~35 %)
-__device__ __forceinline__ uint32_t tile_off(int m, int c) {
-  const int a = m >> 4, h = (m >> 3) & 1, l = m & 7;
-  return (uint32_t)((((a << 3) | l) << 8) | (h << 7) | (((c ^ l ^ a) & 7) << 4));
-}
-
-// Dword jj (k = 2 jj, 2 jj + 1) of column x of the 8 x 8 transpose below (one v_perm_b32).
-__device__ __forceinline__ uint32_t transpose8x8_dword(const uint4 (&r)[8], int x, int jj) {
-  const int i = x >> 1;
-  const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
-  const uint32_t a = i == 0 ? r[2 * jj].x : i == 1 ? r[2 * jj].y : i == 2 ? r[2 * jj].z : r[2 * jj].w;
-  const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
-  return __builtin_amdgcn_perm(b, a, sel);
-}
-// JA consecutive 16-bit columns of one k-row as loaded (JA = 8: 16 bytes, 4: 8 bytes, 2: 4 bytes)
-template <int JA> struct ACols { uint32_t d[JA / 2]; };
-// Dword jj (k = 2 jj, 2 jj + 1) of column x out of 8 k-rows of JA columns each (one v_perm_b32).
-template <int JA>
-__device__ __forceinline__ uint32_t transpose_cols_dword(const ACols<JA> (&r)[8], int x, int jj) {
-  const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
-  return __builtin_amdgcn_perm(r[2 * jj + 1].d[x >> 1], r[2 * jj].d[x >> 1], sel);
-}
-// One output row of the 8 x 8 transpose below: out_x = 8 consecutive k of column x (4 v_perm_b32).
-__device__ __forceinline__ uint4 transpose8x8_row(const uint4 (&r)[8], int x) {
-  const int i = x >> 1;
-  const uint32_t sel = (x & 1) ? 0x07060302u : 0x05040100u;
-  uint32_t d[4];
-#pragma unroll
-  for (int jj = 0; jj < 4; ++jj) {
-    const uint32_t a = i == 0 ? r[2 * jj].x : i == 1 ? r[2 * jj].y : i == 2 ? r[2 * jj].z : r[2 * jj].w;
-    const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
-    d[jj] = __builtin_amdgcn_perm(b, a, sel);
-  }
-  return make_uint4(d[0], d[1], d[2], d[3]);
-}
-
-// r[j] = 8 consecutive columns of k-row j (16-bit elements); out[x] = 8 consecutive k of column x
-__device__ __forceinline__ void transpose8x8_b16(const uint4 (&r)[8], uint4 (&out)[8]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t lo[4], hi[4];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const uint32_t a = i == 0 ? r[2 * jj].x : i == 1 ? r[2 * jj].y : i == 2 ? r[2 * jj].z : r[2 * jj].w;
-      const uint32_t b = i == 0 ? r[2 * jj + 1].x : i == 1 ? r[2 * jj + 1].y : i == 2 ? r[2 * jj + 1].z : r[2 * jj + 1].w;
-      lo[jj] = __builtin_amdgcn_perm(b, a, 0x05040100u);
-      hi[jj] = __builtin_amdgcn_perm(b, a, 0x07060302u);
-    }
-    out[2 * i] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    out[2 * i + 1] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-  }
-}
-
-__device__ __forceinline__ const char* uniform_ptr(const void* p) {
-  const uint64_t v = reinterpret_cast<uint64_t>(p);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
-}
-// 16-byte load from global memory at a wave-uniform base plus a 32-bit per-lane byte offset.  The
-// explicit global address space keeps the access a global_load (a flat load would tie up both
-// memory counters and force full waits).
-__device__ __forceinline__ uint4 load16(const char* base, uint32_t byte_off) {
-  typedef const u32x4_t __attribute__((address_space(1))) * gptr_t;
-  const u32x4_t v = *(gptr_t)(uintptr_t)(reinterpret_cast<uintptr_t>(base) + byte_off);
-  return __builtin_bit_cast(uint4, v);
-}
-// the same for 2 * JA bytes
-template <int JA>
-__device__ __forceinline__ ACols<JA> load_cols(const char* base, uint32_t byte_off) {
-  ACols<JA> r;
-  const uintptr_t a = reinterpret_cast<uintptr_t>(base) + byte_off;
-  if constexpr (JA == 8) {
-    const u32x4_t v = *(const u32x4_t __attribute__((address_space(1)))*)a;
-    r.d[0] = v[0]; r.d[1] = v[1]; r.d[2] = v[2]; r.d[3] = v[3];
-  } else if constexpr (JA == 4) {
-    const u32x2_t v = *(const u32x2_t __attribute__((address_space(1)))*)a;
-    r.d[0] = v[0]; r.d[1] = v[1];
-  } else {
-    static_assert(JA == 2, "columns per lane");
-    r.d[0] = *(const uint32_t __attribute__((address_space(1)))*)a;
-  }
-  return r;
-}
-
-// nothing may be scheduled across this point
-#define PIT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-
-// GATHER_M (A K-minor, rows gathered; B K-major, contiguous k).  CT: 0 = fp32 C, 1 = C in the input type.
-template <bool BF, int EPI, int CT>
-__global__ void __launch_bounds__(256)
-k_gather_m(const GemmArgs g) {
-  constexpr int D = 2;   // depth of the register ring of global loads, in steps
-  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_BYTES];
-  __shared__ int s_rows_a[TM];   // GATHER_M: source row of A per tile row
-  __shared__ int s_rows_c[TM];   // destination row of C per tile row (-1 = skip)
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(PIT_LDS char*)smem;
-
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int wm = wv >> 1, wn = wv & 1;
-
-  // ---------------------------------------------------------------- which tile is this workgroup?
-  // Consecutive workgroup ids go to different XCDs (8, each with its own L2).  Renumber so that XCD
-  // x works on row tiles x, x + 8, x + 16, .. and runs all column tiles of a row tile back to back:
-  // they read the same gathered A rows through the same L2.  (Row tiles stay interleaved over the
-  // XCDs because the grid is sized for the worst case and the surplus row tiles sit at its end.)
-  // With one k-slab per segment (micro-tiles along k) every row tile has its own few B rows and
-  // the plain order measures faster.
-  int tile_row, tile_col;
-  {
-    const int tn = gridDim.x, tm = gridDim.y;
-    const int lin = blockIdx.x + tn * blockIdx.y;
-    const int full = g.slab_per_seg ? 0 : (tm >> 3) << 3;   // row tiles dealt out in rounds of 8
-    if (lin < full * tn) {
-      const int x = lin & 7, i = lin >> 3;
-      tile_row = (i / tn) * 8 + x;
-      tile_col = i % tn;
-    } else {
-      tile_row = lin / tn;
-      tile_col = lin - tile_row * tn;
-    }
-  }
-  const int n0 = tile_col * TN;
-
-  int seg, list_begin, list_len;   // the row-list slice of this tile
-  int k_begin = 0, k_len = 0;      // contiguous k range
-  {
-    // linear row-tile number -> (segment, tile inside segment); every wave does the same search
-    const int tile = tile_row;
-    int acc = 0;
-    seg = -1;
-    int tile_in_seg = 0;
-    for (int s0 = 0; s0 < g.nseg; s0 += 64) {
-      const int s = s0 + lane;
-      int cnt = 0;
-      if (s < g.nseg) cnt = g.seg_ptr[s + 1] - g.seg_ptr[s];
-      const int nt = (cnt + TM - 1) / TM;
-      int inc = nt;
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const int t = __shfl_up(inc, d);
-        if (lane >= d) inc += t;
-      }
-      const int total = __shfl(inc, 63);
-      if (tile < acc + total) {
-        const unsigned long long hit = __ballot(acc + inc > tile);
-        const int l = __builtin_ctzll(hit);
-        seg = s0 + l;
-        tile_in_seg = tile - (acc + __shfl(inc, l) - __shfl(nt, l));
-        break;
-      }
-      acc += total;
-    }
-    if (seg < 0) return;
-    const int sb = g.seg_ptr[seg];
-    const int cnt = g.seg_ptr[seg + 1] - sb;
-    list_begin = sb + tile_in_seg * TM;
-    list_len = min(TM, cnt - tile_in_seg * TM);
-    k_begin = g.slab_per_seg ? seg * g.slab : 0;
-    k_len = g.slab;
-    if (tid < TM) {
-      // rows past the end of the list read the list's last row (a valid address); their results
-      // are never stored
-      const int v = g.idx[list_begin + min(tid, list_len - 1)];
-      s_rows_a[tid] = g.a_gather ? v : list_begin + min(tid, list_len - 1);
-      s_rows_c[tid] = tid < list_len ? (g.c_scatter ? v : list_begin + tid) : -1;
-    }
-    __syncthreads();
-  }
-  seg = __builtin_amdgcn_readfirstlane(seg);
-  list_begin = __builtin_amdgcn_readfirstlane(list_begin);
-  list_len = __builtin_amdgcn_readfirstlane(list_len);
-
-  f32x16_t acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int len = k_len;                           // extent of the k loop (slab width)
-  const int nsteps = (len + TK - 1) / TK;
-  const int tail = len % TK;                       // != 0: the last step is partial
-
-  // ---- loader roles: threads 0..127 fill the A tile, threads 128..255 the B tile (wave-uniform)
-  const bool is_b = __builtin_amdgcn_readfirstlane(tid >> 7) != 0;
-  const int u = tid & 127;
-  const int t_cg = u & 15, t_kg = u >> 4;                               // transposing role: 8 k x 8 columns
-  const int s_chunk = u & 7, s_row = (((u >> 3) & 1) << 3) | (u >> 4);  // straight role (A): rows r, r+8 per 16 lanes
-  const bool transposing = is_b;
-
-  const char* a_bytes = reinterpret_cast<const char*>(g.A);
-  const char* b_bytes = reinterpret_cast<const char*>(g.B) + (int64_t)seg * g.b_seg_stride * 2;
-  const char* src = uniform_ptr(is_b ? b_bytes : a_bytes);
-  const uint32_t pitch = (uint32_t)((is_b ? g.ldb : g.lda) * 2);   // bytes per source row (< 2^24, checked on the host)
-  // transposing role: byte offset of this thread's 8 columns inside a source row
-  const uint32_t col_bytes = (uint32_t)(n0 + t_cg * 8) * 2u;
-
-  uint32_t a_off[8];   // straight role: byte offset of (row of round j, this thread's chunk) at k step 0
-#pragma unroll
-  for (int j = 0; j < 8; ++j) a_off[j] = __umul24((uint32_t)s_rows_a[j * 16 + s_row], pitch) + (uint32_t)(k_begin + s_chunk * 8) * 2u;
-
-  // LDS write offsets (8 per thread) and read offsets (32-row block i of this wave, k-substep ks)
-  uint32_t w_off[8];
-#pragma unroll
-  for (int x = 0; x < 8; ++x) w_off[x] = (transposing ? tile_off(t_cg * 8 + x, t_kg) : tile_off(x * 16 + s_row, s_chunk)) + (is_b ? (uint32_t)A_TILE_BYTES : 0u);
-  uint32_t rd_a[2][4], rd_b[2][4];
-  {
-    const int m = lane & 31, hi = lane >> 5;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        rd_a[i][ks] = tile_off(wm * 64 + i * 32 + m, hi + 2 * ks);
-        rd_b[i][ks] = tile_off(wn * 64 + i * 32 + m, hi + 2 * ks) + (uint32_t)A_TILE_BYTES;
-      }
-  }
-
-  uint4 R[D][8];
-
-  auto issue = [&](int step, uint4 (&r)[8]) {
-    if (is_b) {
-      const int base = k_begin + min(step * TK + t_kg * 8, k_len - 8);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) r[j] = load16(src, __umul24((uint32_t)(base + j), pitch) + col_bytes);
-    } else {
-      // byte distance from this thread's chunk at step 0; a chunk past the slab end re-reads the last one
-      const uint32_t kofs = (uint32_t)((min(step * TK + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) r[j] = load16(src, a_off[j] + kofs);
-    }
-  };
-  // byte offsets of the 8 loads of `step` (same addresses as issue())
-  auto issue_offsets = [&](int step, uint32_t (&off)[8]) {
-    if (is_b) {
-      const int base = k_begin + min(step * TK + t_kg * 8, k_len - 8);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) off[j] = __umul24((uint32_t)(base + j), pitch) + col_bytes;
-    } else {
-      const uint32_t kofs = (uint32_t)((min(step * TK + s_chunk * 8, k_len - 8) - s_chunk * 8) * 2);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) off[j] = a_off[j] + kofs;
-    }
-  };
-  // zero what lies past the end of the k extent (last, partial step only)
-  auto zero_tail = [&](int step, uint4 (&r)[8]) {
-    if (transposing) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (step * TK + t_kg * 8 + j >= len) r[j] = make_uint4(0, 0, 0, 0);
-    } else if (step * TK + s_chunk * 8 >= len) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) r[j] = make_uint4(0, 0, 0, 0);
-    }
-  };
-  // the 8 x 16 B this thread will write to LDS for `step`: transposed (or straight) and, in the
-  // last partial step, with everything past the end of the k extent zeroed
-  auto prepare = [&](int step, uint4 (&r)[8], uint4 (&o)[8], bool may_be_last) {
-    if (may_be_last && tail != 0 && step == nsteps - 1) zero_tail(step, r);
-    if (transposing) {
-      transpose8x8_b16(r, o);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) o[j] = r[j];
-    }
-  };
-  auto read_frags = [&](uint32_t t, int ks, u32x4_t (&af)[2], u32x4_t (&bf)[2]) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      af[i] = lds_read_frag(t + rd_a[i][ks]);
-      bf[i] = lds_read_frag(t + rd_b[i][ks]);
-    }
-  };
-  // One step.  MFMAs of `step` read LDS buffer `buf`; the tile of step + 1, already transposed in
-  // the registers o[], goes to the other buffer; the tile of step + 2 is taken out of ring slot r
-  // and transposed into o[]; the loads of step + 1 + D refill ring slot rl (the one emptied by the
-  // previous step).  A wavefront issues in order and an MFMA keeps the matrix pipe busy for 32
-  // clocks, so everything else is placed BETWEEN consecutive MFMAs, about 30 clocks' worth each:
-  //   MFMA 0..7    one LDS read (operands of the next k-substep), one LDS write, one global load
-  //   MFMA 8..11   one LDS read, a quarter of the transpose (4 v_perm_b32) ... MFMA 12..15 likewise
-  // `steady` = compile-time true in the branch-free loop (all parts on, order pinned).
-  auto body = [&](int step, int buf, uint4 (&o)[8], uint4 (&r)[8], uint4 (&rl)[8],
-                  bool do_write, bool do_prep, bool do_issue, bool steady) {
-    const uint32_t t = lds0 + buf * STAGE_BYTES, tw = lds0 + (buf ^ 1) * STAGE_BYTES;
-    u32x4_t fa[2][2], fb[2][2];
-    read_frags(t, 0, fa[0], fb[0]);
-    if (!steady && do_prep && tail != 0 && step + 2 == nsteps - 1) zero_tail(step + 2, r);
-    uint32_t goff[8];
-    if (do_issue) issue_offsets(step + 1 + D, goff);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int ks = i >> 2, q = i & 3;
-      // operands swapped: the accumulator holds the 32 x 32 block transposed (lane = row of C, registers =
-      // columns, four consecutive ones at a time), which is what the stores below want
-      acc[q >> 1][q & 1] = mfma32<BF>(fb[ks & 1][q & 1], fa[ks & 1][q >> 1], acc[q >> 1][q & 1]);
-      if (i < 12) {   // operands of k-substep ks + 1: A block 0, B block 0, A block 1, B block 1
-        const int nb = (ks + 1) & 1;
-        if (q == 0) fa[nb][0] = lds_read_frag(t + rd_a[0][ks + 1]);
-        if (q == 1) fb[nb][0] = lds_read_frag(t + rd_b[0][ks + 1]);
-        if (q == 2) fa[nb][1] = lds_read_frag(t + rd_a[1][ks + 1]);
-        if (q == 3) fb[nb][1] = lds_read_frag(t + rd_b[1][ks + 1]);
-      }
-      if (i < 8) {
-        if (do_write) lds_write_b128(tw + w_off[i], o[i]);
-        if (do_issue) rl[i] = load16(src, goff[i]);
-      } else if (do_prep) {
-        o[i - 8] = transposing ? transpose8x8_row(r, i - 8) : r[i - 8];
-      }
-      if (steady) PIT_SCHED_FENCE();   // keep the slots in this order (the scheduler would cluster the MFMAs)
-    }
-    PIT_SCHED_FENCE();
-    __syncthreads();
-  };
-
-  if (nsteps > 0) {
-    // prologue: loads of tiles 0 .. D; tile 0 into LDS, tile 1 transposed into o[].  Tile t >= 2
-    // travels through ring slot (t - 2) % D; slot D-1 is filled by step 0.
-    uint4 o[8], r0[8], r1[8];
-    issue(0, r0);
-    issue(min(1, nsteps - 1), r1);
-#pragma unroll
-    for (int s = 0; s + 1 < D; ++s) issue(min(2 + s, nsteps - 1), R[s]);
-    prepare(0, r0, o, true);
-#pragma unroll
-    for (int x = 0; x < 8; ++x) lds_write_b128(lds0 + w_off[x], o[x]);
-    if (nsteps > 1) prepare(1, r1, o, true);
-    __syncthreads();
-
-    int it = 0;
-    // steady state, 4 steps per trip: every step here has step + 2 + D < nsteps; no conditionals
-    // around memory operations
-    for (; it + 5 + D < nsteps; it += 4) {
-#pragma unroll
-      for (int uu = 0; uu < 4; ++uu)
-        body(it + uu, uu & 1, o, R[uu % D], R[(uu + D - 1) % D], true, true, true, true);
-    }
-    // drain
-    for (; it < nsteps; it += 4) {
-#pragma unroll
-      for (int uu = 0; uu < 4; ++uu) {
-        const int step = it + uu;
-        if (step >= nsteps) break;
-        body(step, uu & 1, o, R[uu % D], R[(uu + D - 1) % D], step + 1 < nsteps, step + 2 < nsteps, step + 1 + D < nsteps, false);
-      }
-    }
-  }
-
-  // ---------------------------------------------------------------- SWrite
-  // lane l holds row (l % 32) of each of its two row blocks and, per register quad, 4 consecutive
-  // columns: one row number and (optionally) one gate value per lane and block, 16-byte stores
-  // (8-byte ones for 16-bit output), 16 store instructions per wave instead of 64 scalar ones
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int r = wm * 64 + i * 32 + (lane & 31);
-    const int64_t crow = s_rows_c[r];
-    if (crow < 0) continue;
-    float scale = 1.f;
-    if constexpr (EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const int col = n0 + wn * 64 + j * 32 + 8 * gq + 4 * (lane >> 5);
-        float v[4];
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          v[x] = acc[i][j][4 * gq + x];
-          if constexpr (EPI == EPI_GELU) v[x] = gelu_erf_fast(v[x]);
-          if constexpr (EPI == EPI_STORE) v[x] *= scale;
-        }
-        if constexpr (CT == 0) {
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C) + crow * g.ldc + col) = make_float4(v[0], v[1], v[2], v[3]);
-        } else {
-          const uint32_t lo = (uint32_t)f32_to_in<BF>(v[0]) | ((uint32_t)f32_to_in<BF>(v[1]) << 16);
-          const uint32_t hi = (uint32_t)f32_to_in<BF>(v[2]) | ((uint32_t)f32_to_in<BF>(v[3]) << 16);
-          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.C) + crow * g.ldc + col) = make_uint2(lo, hi);
-        }
-      }
-    }
-  }
-}
 
 // ------------------------------------------------------------------------------------------------
 // GATHER_K, register-direct: no LDS and no barrier inside the k loop.
@@ -1118,68 +677,42 @@ __global__ void __launch_bounds__(256) k_zero_rows(void* C, int64_t ld_bytes, in
 
 // compute units of the current device rounded down to a multiple of 8 (one share per XCD)
 static int compute_units() {
-  static int cached[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
-    cached[dev] = n & ~7;
-  }
-  return cached[dev];
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+  return n & ~7;
 }
 
-template <bool BF, bool GK, int EPI, int CT>
-static int launch_one(const GemmArgs& g, dim3 grid, hipStream_t st) {
-  if constexpr (GK) {
-    static_assert(EPI == EPI_STORE, "GATHER_K has the plain store epilogue only");
-    // one workgroup fits on a compute unit: with more tiles than compute units the workgroups loop
-    const int total = (int)(grid.x * grid.y), cus = compute_units();
-    if (g.slab == 64 || g.slab == 32) {
-      // lower tiles: two-wave workgroups; as many as the registers let a compute unit hold (64 rows: two,
-      // 32 rows: four, i.e. two waves per SIMD)
-      const int resident = (g.slab == 64 ? 2 : 4) * cus;
-      const unsigned wgs = (unsigned)(total <= resident ? total : resident);
-      if (g.slab == 64) hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 4>), dim3(wgs), dim3(128), 0, st, g, (int)grid.y);
-      else              hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 2>), dim3(wgs), dim3(128), 0, st, g, (int)grid.y);
-    } else if (total >= 2 * cus) {      // two workgroups of two waves per compute unit
-      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 8>), dim3((unsigned)(2 * cus)), dim3(128), 0, st, g, (int)grid.y);
-    } else {
-      const unsigned wgs = (unsigned)(total <= cus ? total : cus);
-      hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 4, 8>), dim3(wgs), dim3(256), 0, st, g, (int)grid.y);
-    }
-    PIT_LAUNCH_CHECK();
-    return PIT_OK;
+template <bool BF, int CT>
+static int launch_gather_k(const GemmArgs& g, int tm_tiles, hipStream_t st) {
+  // one workgroup of the 128-row tile fits on a compute unit: with more tiles than compute units the workgroups loop
+  const int total = (int)(g.N / TN) * tm_tiles, cus = compute_units();
+  if (g.slab == 64 || g.slab == 32) {
+    // lower tiles: two-wave workgroups; as many as the registers let a compute unit hold (64 rows: two,
+    // 32 rows: four, i.e. two waves per SIMD)
+    const int resident = (g.slab == 64 ? 2 : 4) * cus;
+    const unsigned wgs = (unsigned)(total <= resident ? total : resident);
+    if (g.slab == 64) hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 4>), dim3(wgs), dim3(128), 0, st, g, tm_tiles);
+    else              hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 2>), dim3(wgs), dim3(128), 0, st, g, tm_tiles);
+  } else if (total >= 2 * cus) {      // two workgroups of two waves per compute unit
+    hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 2, 8>), dim3((unsigned)(2 * cus)), dim3(128), 0, st, g, tm_tiles);
   } else {
-    hipLaunchKernelGGL((k_gather_m<BF, EPI, CT>), grid, dim3(256), 0, st, g);
-    PIT_LAUNCH_CHECK();
-    return PIT_OK;
+    const unsigned wgs = (unsigned)(total <= cus ? total : cus);
+    hipLaunchKernelGGL((k_gather_k_direct<BF, CT, 4, 8>), dim3(wgs), dim3(256), 0, st, g, tm_tiles);
   }
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
 }
 
-template <bool BF>
-static int launch_bf(bool gather_k, int epi, int ct, const GemmArgs& g, dim3 grid, hipStream_t st) {
-  if (gather_k) {
-    if (epi != EPI_STORE) return PIT_EINVAL;
-    return ct ? launch_one<BF, true, EPI_STORE, 1>(g, grid, st) : launch_one<BF, true, EPI_STORE, 0>(g, grid, st);
-  }
-  switch (epi) {
-    case EPI_STORE:  return ct ? launch_one<BF, false, EPI_STORE, 1>(g, grid, st) : launch_one<BF, false, EPI_STORE, 0>(g, grid, st);
-    case EPI_GELU:   return ct ? launch_one<BF, false, EPI_GELU, 1>(g, grid, st) : PIT_EINVAL;
-    default: return PIT_EINVAL;
-  }
-}
-
-int launch_sread_gemm(bool bf, bool gather_k, int epi, int c_is_in_type, const GemmArgs& g, int max_tiles, hipStream_t st) {
-  if (max_tiles <= 0 || g.N <= 0) return PIT_OK;
-  // the kernel addresses each operand with 32-bit byte offsets from a per-segment base and
-  // multiplies row numbers by the row pitch in 24 bits
-  const int64_t a_rows = gather_k ? g.K : g.M;
-  if (g.lda * 2 >= (1ll << 24) || g.ldb * 2 >= (1ll << 24) || a_rows >= (1ll << 24) || g.K >= (1ll << 24)) return PIT_ESHAPE;
-  if (a_rows * g.lda * 2 >= (1ll << 32) || (int64_t)g.K * g.ldb * 2 >= (1ll << 32)) return PIT_ESHAPE;
-  dim3 grid((unsigned)(g.N / TN), (unsigned)max_tiles);
-  return bf ? launch_bf<true>(gather_k, epi, c_is_in_type, g, grid, st)
-            : launch_bf<false>(gather_k, epi, c_is_in_type, g, grid, st);
+// GATHER_K: tm_tiles = number of row tiles = segments of the index
+static int launch_sread_gemm_k(bool bf, int c_is_in_type, const GemmArgs& g, int tm_tiles, hipStream_t st) {
+  if (tm_tiles <= 0 || g.N <= 0) return PIT_OK;
+  // the kernel addresses each operand with 32-bit byte offsets from a uniform base and multiplies row
+  // numbers by the row pitch in 24 bits
+  if (g.lda * 2 >= (1ll << 24) || g.ldb * 2 >= (1ll << 24) || (int64_t)g.K >= (1ll << 24)) return PIT_ESHAPE;
+  if ((int64_t)g.K * g.lda * 2 >= (1ll << 32) || (int64_t)g.K * g.ldb * 2 >= (1ll << 32)) return PIT_ESHAPE;
+  if (bf) return c_is_in_type ? launch_gather_k<true, 1>(g, tm_tiles, st) : launch_gather_k<true, 0>(g, tm_tiles, st);
+  return c_is_in_type ? launch_gather_k<false, 1>(g, tm_tiles, st) : launch_gather_k<false, 0>(g, tm_tiles, st);
 }
 
 int launch_zero_rows(void* C, int64_t ld_bytes, int M, int64_t row_bytes, hipStream_t st) {
@@ -1221,7 +754,7 @@ extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void
     if (ix->nseg != M / mt) return PIT_ECAPACITY;
     if (K > 0 && lda < M) return PIT_EINVAL;
     g.slab = mt;       // GATHER_K: the tile height (= micro-tile height of the index)
-    return launch_sread_gemm(in_dt == PIT_BF16, true, EPI_STORE, c_dt != PIT_F32, g, ix->nseg, st);
+    return launch_sread_gemm_k(in_dt == PIT_BF16, c_dt != PIT_F32, g, ix->nseg, st);
   }
 
   // GATHER_M
@@ -1235,14 +768,13 @@ extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void
   if (ix->nseg != K / mt) return PIT_ECAPACITY;
   if (lda < K) return PIT_EINVAL;
   g.slab = mt; g.a_gather = 1; g.c_scatter = 1; g.slab_per_seg = 1;
-  const int tiles_per_seg = (int)ceil_div(M, TM);
   if (ix->nseg == 1) {
     if (zero_uncovered) {
       if (c_esize == 4) hipLaunchKernelGGL(k_zero_uncovered<4>, dim3((unsigned)ceil_div(M, 4)), dim3(256), 0, st, d_C, ldc, M, N, ix->seg_ptr, ix->idx);
       else              hipLaunchKernelGGL(k_zero_uncovered<2>, dim3((unsigned)ceil_div(M, 4)), dim3(256), 0, st, d_C, ldc, M, N, ix->seg_ptr, ix->idx);
       PIT_LAUNCH_CHECK();
     }
-    return launch_sread_gemm(in_dt == PIT_BF16, false, EPI_STORE, c_dt != PIT_F32, g, tiles_per_seg, st);
+    return launch_gather_m(in_dt == PIT_BF16, EPI_STORE, c_dt != PIT_F32, g, M, st);
   }
   if (c_dt != PIT_F32) return PIT_EINVAL;
   // several k-slabs per row: C-stationary strips (every element of C is written, nothing to clear)

@@ -1,0 +1,353 @@
+// GATHER_M: SRead -> dense MFMA tile -> SWrite with m as the PIT-axis (paper Section 3.1, sparse kernel
+// template; Table 1, MatMul axis m), for gfx950.  Used for whole-row micro-tiles: the valid token rows
+// of a padded batch, and both matmuls of the mixture-of-experts FFN.
+//
+// One workgroup = 2 x 2 wavefronts computes a (64 WM) x (64 WN) tile of C; a wave owns (32 WM) x (32 WN)
+// of it as WM x WN blocks of v_mfma_f32_32x32x16 (bf16 or f16 in, fp32 accumulate).
+//
+// SRead.  The tile's row numbers come from the index once (into LDS).  Per step of 32 along k, the
+// operands travel global -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane, no registers in
+// between), into a ring of NST stages so that NST - 1 steps of loads are in flight while one is
+// multiplied.  A direct load writes 1 KiB of LDS contiguously per wavefront but takes its 64 source
+// addresses per lane, so the gather (which row) and the bank swizzle (which 16 bytes of the row) are
+// both expressed by the choice of source address:
+//   A tile [64 WM rows][32 k]   (K-minor, 64 B per row).  One load instruction = 16 listed rows x 64 B.
+//                               16-byte chunk c of row r lies at slot c ^ ((r >> 2) & 3); operands are
+//                               read with ds_read_b128 (8 consecutive k of one row per lane).
+//   B tile [32 k][64 WN cols]   (K-major as stored, 128 WN B per k-row).  One load instruction =
+//                               1 KiB of consecutive k-rows.  64-byte chunk q of k-row k lies at
+//                               position q ^ (k & 3); operands are read with the transposing LDS read
+//                               (ds_read_b64_tr_b16: in each group of 16 lanes, lane i receives column i
+//                               of the four k-rows addressed by lanes 4 j .. 4 j + 3), two reads giving the 8
+//                               consecutive k of one column that the MFMA wants.  Nothing is transposed
+//                               by vector instructions and nothing is written to LDS from registers.
+// Synchronisation: the loads are inline assembly, invisible to the compiler's counters; a wave waits
+// for its own loads of a stage with an explicit s_waitcnt vmcnt(n) that leaves the younger stages in
+// flight, then the workgroup meets at one barrier per stage, after which the stage that was read before
+// the barrier may be overwritten by the loads of stage s + NST - 1.
+//
+// SWrite.  Every 32 x 32 block is computed transposed (operands swapped), so a lane holds one row of C
+// and four consecutive columns per register quad: one row number (and gate) per lane, 16-byte stores to
+// the row the index names (or to compact rows), optionally GELU + rounding to the input type.
+#include "pit_gemm.hpp"
+#include "pit_gemm_dev.hpp"
+
+namespace pit {
+namespace {
+
+// Direct global -> LDS load of 16 bytes per lane: lane i's bytes land at lds_wave_base + 16 i.
+// `base` and `lds_wave_base` are wave-uniform.
+__device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_wave_base) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(m0v), "v"(byte_off), "s"(reinterpret_cast<uint64_t>(base)) : "memory", "m0");
+}
+__device__ __forceinline__ uint2 lds_tr(uint32_t addr) {
+  return __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((PIT_LDS v4i16_t*)(uintptr_t)addr));
+}
+// wait until at most n vector-memory operations of this wavefront are outstanding (gfx9 encoding:
+// vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait"); LDS accesses that
+// follow in program order stay behind it
+#define PIT_WAIT_VMCNT(n) do { __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14)); \
+                               asm volatile("" ::: "memory"); } while (0)
+// workgroup barrier that waits for this wave's LDS operations only (not for vector-memory operations:
+// the younger stages' loads stay in flight across it)
+#define PIT_LDS_BARRIER() do { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); __builtin_amdgcn_s_barrier(); \
+                               asm volatile("" ::: "memory"); } while (0)
+
+// GM x GN = arrangement of the four waves over the tile (2 x 2 or 1 x 4); a wave owns WM x WN blocks of 32 x 32.
+template <int WM, int WN, int NST, int GN> struct MTile {
+  static constexpr int GM = 4 / GN;
+  static constexpr int TMW = 32 * WM * GM, TNW = 32 * WN * GN, KS = 32;
+  static constexpr int A_STAGE = TMW * KS * 2, B_STAGE = KS * TNW * 2, STAGE = A_STAGE + B_STAGE;
+  static constexpr int LA = TMW / 64, LB = TNW / 64;   // load instructions per wave and stage: A, B
+  static constexpr int LOADS = LA + LB;
+  static_assert(GN == 2 || GN == 4, "wave arrangement");
+  static_assert(TMW % 64 == 0, "rows of a tile");
+  static_assert(TNW == 128 || TNW == 256, "the B swizzle assumes k-rows of 256 or 512 bytes");
+  static_assert(NST >= 2 && NST <= 6 && (NST - 1) * LOADS < 64, "stages in flight must fit the 6-bit counter");
+};
+
+template <bool BF, int EPI, int CT, int WM, int WN, int NST, int GN>
+__global__ void __launch_bounds__(256, 2)
+k_gather_m_lds(const GemmArgs g) {
+  using T = MTile<WM, WN, NST, GN>;
+  constexpr int TMW = T::TMW, TNW = T::TNW, KS = T::KS, LA = T::LA, LB = T::LB;
+  __shared__ __attribute__((aligned(1024))) char smem[NST * T::STAGE];
+  __shared__ int s_rows_a[TMW];   // source row of A per tile row
+  __shared__ int s_rows_c[TMW];   // destination row of C per tile row (-1 = skip)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(PIT_LDS char*)smem;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wv / GN, wn = wv % GN;
+
+  // ---------------------------------------------------------------- which tile is this workgroup?
+  // Consecutive workgroup ids go to different XCDs (8, each with its own L2).  Renumber so that XCD
+  // x works on row tiles x, x + 8, x + 16, .. and runs all column tiles of a row tile back to back:
+  // they read the same gathered A rows through the same L2.  (Row tiles stay interleaved over the
+  // XCDs because the grid is sized for the worst case and the surplus row tiles sit at its end.)
+  int tile_row, tile_col;
+  {
+    const int tn = gridDim.x, tm = gridDim.y;
+    const int lin = blockIdx.x + tn * blockIdx.y;
+    const int full = (tm >> 3) << 3;   // row tiles dealt out in rounds of 8
+    if (lin < full * tn) {
+      const int x = lin & 7, i = lin >> 3;
+      tile_row = (i / tn) * 8 + x;
+      tile_col = i % tn;
+    } else {
+      tile_row = lin / tn;
+      tile_col = lin - tile_row * tn;
+    }
+  }
+  const int n0 = tile_col * TNW;
+
+  int seg, list_len;
+  {
+    // linear row-tile number -> (segment, tile inside segment); every wave does the same search
+    const int tile = tile_row;
+    int acc = 0;
+    seg = -1;
+    int tile_in_seg = 0;
+    for (int s0 = 0; s0 < g.nseg; s0 += 64) {
+      const int s = s0 + lane;
+      int cnt = 0;
+      if (s < g.nseg) cnt = g.seg_ptr[s + 1] - g.seg_ptr[s];
+      const int nt = (cnt + TMW - 1) / TMW;
+      int inc = nt;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_up(inc, d);
+        if (lane >= d) inc += t;
+      }
+      const int total = __shfl(inc, 63);
+      if (tile < acc + total) {
+        const unsigned long long hit = __ballot(acc + inc > tile);
+        const int l = __builtin_ctzll(hit);
+        seg = s0 + l;
+        tile_in_seg = tile - (acc + __shfl(inc, l) - __shfl(nt, l));
+        break;
+      }
+      acc += total;
+    }
+    if (seg < 0) return;
+    const int sb = g.seg_ptr[seg];
+    const int cnt = g.seg_ptr[seg + 1] - sb;
+    const int list_begin = sb + tile_in_seg * TMW;
+    list_len = min(TMW, cnt - tile_in_seg * TMW);
+    for (int r = tid; r < TMW; r += 256) {
+      // rows past the end of the list read the list's last row (a valid address); their results
+      // are never stored
+      const int v = g.idx[list_begin + min(r, list_len - 1)];
+      s_rows_a[r] = g.a_gather ? v : list_begin + min(r, list_len - 1);
+      s_rows_c[r] = r < list_len ? (g.c_scatter ? v : list_begin + r) : -1;
+    }
+    __syncthreads();
+  }
+  seg = __builtin_amdgcn_readfirstlane(seg);
+
+  f32x16_t acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int nsteps = g.slab / KS;                  // the k extent is a multiple of 32 (checked on the host)
+
+  // ---------------------------------------------------------------- loader: source offsets per lane
+  const char* a_src = uniform_ptr(g.A);
+  const char* b_src = uniform_ptr(reinterpret_cast<const char*>(g.B) + (int64_t)seg * g.b_seg_stride * 2);
+  const uint32_t pitch_a = (uint32_t)(g.lda * 2), pitch_b = (uint32_t)(g.ldb * 2);
+  // A: load instruction j (this wave: j = wv + 4 jj) brings tile rows 16 j .. 16 j + 15; lane l -> row
+  // 16 j + l / 4, slot l % 4, which holds source chunk (l % 4) ^ ((row >> 2) & 3)
+  uint32_t a_off[LA];
+#pragma unroll
+  for (int jj = 0; jj < LA; ++jj) {
+    const int r = 16 * (wv + 4 * jj) + (lane >> 2);
+    const int c = (lane & 3) ^ ((r >> 2) & 3);
+    a_off[jj] = __umul24((uint32_t)s_rows_a[r], pitch_a) + (uint32_t)(c * 16);
+  }
+  // B: a k-row of the tile is SPR slots of 16 B; load instruction j brings k-rows RPI j .. RPI j + RPI - 1;
+  // lane l -> k-row RPI j + l / SPR, slot s = l % SPR, which holds source chunk ((s >> 2) ^ (k & 3)) * 4 + s % 4
+  constexpr int SPR = TNW / 8, RPI = 64 / SPR;
+  uint32_t b_off[LB];
+#pragma unroll
+  for (int jj = 0; jj < LB; ++jj) {
+    const int kk = RPI * (wv + 4 * jj) + lane / SPR;
+    const int s = lane % SPR;
+    const int q = (s >> 2) ^ (kk & 3);
+    b_off[jj] = __umul24((uint32_t)kk, pitch_b) + (uint32_t)((n0 + q * 32 + (s & 3) * 8) * 2);
+  }
+  const uint32_t b_step = 32u * pitch_b;           // bytes between two stages of B
+  auto issue = [&](int t, int u) {                    // stage t into buffer u = t % NST
+    const uint32_t buf = lds0 + (uint32_t)(u * T::STAGE);
+    const uint32_t ka = (uint32_t)t * 64u, kb = (uint32_t)t * b_step;
+#pragma unroll
+    for (int jj = 0; jj < LA; ++jj) dma16(a_src, a_off[jj] + ka, buf + (uint32_t)((wv + 4 * jj) * 1024));
+#pragma unroll
+    for (int jj = 0; jj < LB; ++jj) dma16(b_src, b_off[jj] + kb, buf + (uint32_t)(T::A_STAGE + (wv + 4 * jj) * 1024));
+  };
+
+  // ---------------------------------------------------------------- operand reads: lane constants
+  // A: row block i, k-substep ks -> row wm * 32 WM + 32 i + lane % 32, chunk 2 ks + lane / 32 (at slot chunk ^ xa,
+  //    xa = (row >> 2) & 3: the row's other bits are multiples of 32)
+  // B: column block j, k-substep ks -> k-rows 16 ks + 8 h + kq (+ 4), 64-byte chunk (wn WN + j) ^ kq
+  // Every address is a per-lane constant plus a compile-time offset (stage, row block, substep).
+  const int h = lane >> 5, xa = (lane >> 2) & 3, kq = (lane & 15) >> 2;
+  uint32_t a_rd[2], b_rd[WN];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+    a_rd[ks] = lds0 + (uint32_t)((wm * 32 * WM + (lane & 31)) * 64 + (((2 * ks + h) ^ xa) << 4));
+#pragma unroll
+  for (int j = 0; j < WN; ++j)
+    b_rd[j] = lds0 + (uint32_t)(T::A_STAGE + (8 * h + kq) * (TNW * 2) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8 +
+                                (((wn * WN + j) ^ kq) << 6));
+  // row blocks of this wave that hold at least one listed row (a tile at the end of a segment, or a segment
+  // with few rows -- an expert with few tokens -- leaves the others without work: no operand reads, no MFMAs)
+  const int live_i = __builtin_amdgcn_readfirstlane(max(0, min(WM, (list_len - wm * 32 * WM + 31) >> 5)));
+
+  struct Frags { u32x4_t a[WM], b[WN]; };
+  auto read_frags = [&](int u, int ks, Frags& f) {     // u = buffer of the stage (compile-time after unrolling)
+    const uint32_t so = (uint32_t)(u * T::STAGE);
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+      if (i < live_i) f.a[i] = lds_read_frag(a_rd[ks] + so + (uint32_t)(i * 2048));
+    if (live_i > 0)
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+      const uint32_t at = b_rd[j] + so + (uint32_t)(ks * 16 * (TNW * 2));
+      const uint2 lo = lds_tr(at), hi = lds_tr(at + 4 * (TNW * 2));
+      f.b[j] = u32x4_t{lo.x, lo.y, hi.x, hi.y};
+    }
+  };
+  auto mfmas = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+      if (i < live_i) {
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          // operands swapped: the accumulator holds the 32 x 32 block transposed (lane = row of C,
+          // registers = columns, four consecutive ones at a time), which is what the stores below want
+          acc[i][j] = mfma32<BF>(f.b[j], f.a[i], acc[i][j]);
+      }
+  };
+
+  // wait until this wave's loads of a stage have landed while `younger` later stages stay in flight
+  auto wait_stage = [&](int younger) {
+    if constexpr (NST >= 6) { if (younger >= 5) { PIT_WAIT_VMCNT(5 * T::LOADS); return; } }
+    if constexpr (NST >= 5) { if (younger == 4) { PIT_WAIT_VMCNT(4 * T::LOADS); return; } }
+    if constexpr (NST >= 4) { if (younger == 3) { PIT_WAIT_VMCNT(3 * T::LOADS); return; } }
+    if constexpr (NST >= 3) { if (younger == 2) { PIT_WAIT_VMCNT(2 * T::LOADS); return; } }
+    if (younger == 1) { PIT_WAIT_VMCNT(1 * T::LOADS); return; }
+    PIT_WAIT_VMCNT(0);
+  };
+
+  // Pipeline.  Stage s is multiplied in two halves (k-substeps 0 and 1).  Between them the wave waits for its
+  // loads of stage s + 1 and the workgroup meets at a barrier: after it every wave holds stage s in registers,
+  // so buffer s % NST takes the loads of stage s + NST, and stage s + 1 has landed for everyone, so the
+  // operands of its first half are requested before the MFMAs of the second half of stage s -- every LDS read
+  // has a group of MFMAs to hide behind, and NST - 1 stages of loads are in flight.
+  if (nsteps > 0) {
+#pragma unroll
+    for (int t = 0; t < NST; ++t)
+      if (t < nsteps) issue(t, t);
+    wait_stage(min(NST - 1, nsteps - 1));
+    PIT_LDS_BARRIER();
+    Frags f0, f1;
+    read_frags(0, 0, f0);
+    for (int s0 = 0; s0 < nsteps; s0 += NST) {
+#pragma unroll
+      for (int u = 0; u < NST; ++u) {
+        const int s = s0 + u;
+        if (s >= nsteps) break;
+        read_frags(u, 1, f1);
+        mfmas(f0);
+        if (s + 1 < nsteps) {
+          wait_stage(min(NST - 2, nsteps - 2 - s));
+          PIT_LDS_BARRIER();
+          if (s + NST < nsteps) issue(s + NST, u);
+          read_frags((u + 1) % NST, 0, f0);
+        }
+        mfmas(f1);
+      }
+    }
+  }
+
+  // ---------------------------------------------------------------- SWrite
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    const int r = wm * 32 * WM + i * 32 + (lane & 31);
+    const int64_t crow = s_rows_c[r];
+    if (crow < 0) continue;
+    float scale = 1.f;
+    if constexpr (EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        const int col = n0 + wn * 32 * WN + j * 32 + 8 * gq + 4 * (lane >> 5);
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          v[x] = acc[i][j][4 * gq + x];
+          if constexpr (EPI == EPI_GELU) v[x] = gelu_erf_fast(v[x]);
+          if constexpr (EPI == EPI_STORE) v[x] *= scale;
+        }
+        if constexpr (CT == 0) {
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C) + crow * g.ldc + col) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+          const uint32_t lo = (uint32_t)f32_to_in<BF>(v[0]) | ((uint32_t)f32_to_in<BF>(v[1]) << 16);
+          const uint32_t hi = (uint32_t)f32_to_in<BF>(v[2]) | ((uint32_t)f32_to_in<BF>(v[3]) << 16);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.C) + crow * g.ldc + col) = make_uint2(lo, hi);
+        }
+      }
+    }
+  }
+}
+
+template <bool BF, int EPI, int CT, int WM, int WN, int NST, int GN = 2>
+int launch_cfg(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
+  using T = MTile<WM, WN, NST, GN>;
+  const int64_t max_tiles = total_rows / T::TMW + g.nseg;      // sum over segments of ceil(count / TMW)
+  if (max_tiles > 65535) return PIT_ESHAPE;
+  dim3 grid((unsigned)(g.N / T::TNW), (unsigned)max_tiles);
+  hipLaunchKernelGGL((k_gather_m_lds<BF, EPI, CT, WM, WN, NST, GN>), grid, dim3(256), 0, st, g);
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
+}
+
+// Tile shape by the shape of the product.  128 x 256 (a wave owns 64 x 128) where N allows: fewer bytes through
+// LDS per MFMA and fewer workgroups' worth of set-up than 128 x 128.  (Measured on the padded-batch product,
+// 8364 x 1024 x 4096: 128 x 128 with a ring of 4 stages 126-130 us, 256 x 128 115-121, 128 x 256 112-119; on the
+// mixture-of-experts call 209-211, 240-271 (rows of small experts are padded to 256) and 194-202 us.)
+template <bool BF, int EPI, int CT>
+int launch_shape(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
+  if (g.N % 256 == 0) return launch_cfg<BF, EPI, CT, 2, 4, 3>(g, total_rows, st);
+  return launch_cfg<BF, EPI, CT, 2, 2, 4>(g, total_rows, st);
+}
+
+template <bool BF>
+int launch_bf(int epi, int ct, const GemmArgs& g, int64_t total_rows, hipStream_t st) {
+  switch (epi) {
+    case EPI_STORE: return ct ? launch_shape<BF, EPI_STORE, 1>(g, total_rows, st) : launch_shape<BF, EPI_STORE, 0>(g, total_rows, st);
+    case EPI_GELU:  return ct ? launch_shape<BF, EPI_GELU, 1>(g, total_rows, st) : PIT_EINVAL;
+    default: return PIT_EINVAL;
+  }
+}
+
+}  // namespace
+
+int launch_gather_m(bool bf, int epi, int c_is_in_type, const GemmArgs& g, int64_t total_rows, hipStream_t st) {
+  if (total_rows <= 0 || g.N <= 0 || g.nseg <= 0) return PIT_OK;
+  if (g.slab % 32 || g.N % 128) return PIT_ESHAPE;
+  // the kernel addresses each operand with 32-bit byte offsets from a per-segment base and multiplies
+  // row numbers by the row pitch in 24 bits
+  if (g.lda * 2 >= (1ll << 24) || g.ldb * 2 >= (1ll << 24) || (int64_t)g.M >= (1ll << 24) || (int64_t)g.K >= (1ll << 24)) return PIT_ESHAPE;
+  if ((int64_t)g.M * g.lda * 2 >= (1ll << 32) || (int64_t)g.K * g.ldb * 2 >= (1ll << 32)) return PIT_ESHAPE;
+  return bf ? launch_bf<true>(epi, c_is_in_type, g, total_rows, st) : launch_bf<false>(epi, c_is_in_type, g, total_rows, st);
+}
+
+}  // namespace pit

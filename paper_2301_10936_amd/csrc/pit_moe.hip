@@ -66,7 +66,6 @@ extern "C" int pit_moe_dispatch_gemm(const void* d_X, const int32_t* d_expert_id
   if (rc != PIT_OK) return rc;
 
   void* H = ws + L.h_off;
-  const int max_tiles = T / TM + E;   // sum over experts of ceil(count / 128) <= T/128 + E
   const bool bf = in_dt == PIT_BF16;
 
   GemmArgs g1 = {};
@@ -74,7 +73,7 @@ extern "C" int pit_moe_dispatch_gemm(const void* d_X, const int32_t* d_expert_id
   g1.C = H; g1.ldc = d_ff; g1.seg_ptr = ix.seg_ptr; g1.idx = ix.idx; g1.gate = nullptr;
   g1.nseg = E; g1.M = T; g1.N = d_ff; g1.K = d_model;
   g1.slab = d_model; g1.a_gather = 1; g1.c_scatter = 0; g1.slab_per_seg = 0;
-  rc = launch_sread_gemm(bf, false, act == 0 ? EPI_GELU : EPI_STORE, 1, g1, max_tiles, st);
+  rc = launch_gather_m(bf, act == 0 ? EPI_GELU : EPI_STORE, 1, g1, T, st);
   if (rc != PIT_OK) return rc;
 
   GemmArgs g2 = {};
@@ -82,5 +81,5 @@ extern "C" int pit_moe_dispatch_gemm(const void* d_X, const int32_t* d_expert_id
   g2.C = d_Y; g2.ldc = d_model; g2.seg_ptr = ix.seg_ptr; g2.idx = ix.idx; g2.gate = d_gate;
   g2.nseg = E; g2.M = T; g2.N = d_model; g2.K = d_ff;
   g2.slab = d_ff; g2.a_gather = 0; g2.c_scatter = 1; g2.slab_per_seg = 0;
-  return launch_sread_gemm(bf, false, EPI_STORE, y_dt != PIT_F32, g2, max_tiles, st);
+  return launch_gather_m(bf, EPI_STORE, y_dt != PIT_F32, g2, T, st);
 }
