@@ -62,6 +62,33 @@ def _time_steps(step, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
+def _group_time(fn, groups=4, per_group=8):
+    """Seconds per call of fn() from groups of back-to-back calls between two events (an event pair around one
+    launch would also measure the dispatch gap)."""
+    import torch
+    for _ in range(3):
+        fn()
+    ev = _events(2 * groups)
+    for gi in range(groups):
+        ev[2 * gi].record()
+        for _ in range(per_group):
+            fn()
+        ev[2 * gi + 1].record()
+    torch.cuda.synchronize()
+    return sum(ev[2 * gi].elapsed_time(ev[2 * gi + 1]) for gi in range(groups)) / (groups * per_group) * 1e-3
+
+
+def _roofline(bound, achieved, kernel, note=None):
+    """A roofline block like the headline's for one of the other workloads: the dominant kernel's algorithmic
+    FLOPs (or bytes) per launch over its duration measured in this run."""
+    peak, unit = (MFMA_PEAK_TFLOPS, "TFLOP/s") if bound == "mfma" else (HBM_PEAK_GBS, "GB/s")
+    r = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+         "frac": round(achieved / peak, 4), "traffic": None, "traffic_source": None}
+    if note:
+        r["note"] = note
+    return r
+
+
 def _read_traffic(name):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), kept as a small
     text summary under profiles/; None when no such measurement is committed."""
@@ -193,26 +220,40 @@ def _cpu_oracle_leg(ws, eff_flops, MT, budget_s=12.0):
                       f"2048x8192x2048 each, inputs cycled through the pool) in {dt:.1f} s"}
 
 
-def bench_relu_ffn_correlated(pit, wl, steps, warmup, pool=4):
-    """Same shape as the headline workload with zeros correlated across tokens (a channel is live
-    for a token block only with some probability): the regime where whole k-rows drop out."""
+def bench_relu_ffn_correlated(pit, wl, steps, warmup, pool=4, live_block=128, live_offset=0):
+    """Same shape as the headline workload with zeros correlated across tokens (a channel is live for a run of
+    `live_block` tokens starting at `live_offset` only with probability 0.25): the regime where whole k-rows drop
+    out.  Runs of 128 tokens at offset 0 coincide with the 128-row tile; runs of 32 tokens, and runs of 128
+    starting at token 64, do not.  The step is timed at each tile height the kernel offers (the index is built at
+    that micro-tile height) and through Algorithm 1 (pit_select_and_run_gemm with the profiled costs)."""
     import numpy as np
     import torch
-    M, K, N, MT = 2048, 8192, 2048, 128
-    ws = [wl.relu_ffn(M=M, K=K, N=N, call=c, channel_live_prob=0.25) for c in range(pool)]
+    M, K, N = 2048, 8192, 2048
+    ws = [wl.relu_ffn(M=M, K=K, N=N, call=c, channel_live_prob=0.25, live_block=live_block, live_offset=live_offset)
+          for c in range(pool)]
     W = _to_dev(ws[0].W)
     Xts = [_to_dev(w.Xt) for w in ws]
     eff = float(np.mean([2.0 * _count_nonzero_microtiles(w.Xt, 32) * 32 * N for w in ws]))
-    ix = pit.PitIndex.empty(M // MT, (M // MT) * K)
-    wsb = torch.empty(pit.pit_build_index_workspace(K, M, 1, MT, 0), dtype=torch.uint8, device="cuda")
     C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    by_mt = {}
+    for MT in (128, 64, 32):
+        ix = pit.PitIndex.empty(M // MT, (M // MT) * K)
+        wsb = torch.empty(pit.pit_build_index_workspace(K, M, 1, MT, 0), dtype=torch.uint8, device="cuda")
 
-    def step(i):
-        Xt = Xts[i % pool]
-        pit.pit_build_index(Xt, 1, MT, 0, out=ix, ws=wsb)
-        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, MT, M, N, K, out=C)
+        def step(i):
+            Xt = Xts[i % pool]
+            pit.pit_build_index(Xt, 1, MT, 0, out=ix, ws=wsb)
+            pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, MT, M, N, K, out=C)
 
-    sec = _time_steps(step, steps, warmup)
+        by_mt[MT] = _time_steps(step, steps, warmup)
+    # Algorithm 1: CoverAlgo on the first activation as the sparsity sample, then the winner on every step
+    cands = _gather_k_candidates(pit)
+    num = [[int(pit.pit_cover_count(Xts[0], 1, c["mt_cols"]).item()) for c in cands]]
+    grid = [[K * (M // c["mt_cols"]) for c in cands]]
+    wsel = torch.empty(pit.pit_select_and_run_gemm_workspace(M, K), dtype=torch.uint8, device="cuda")
+    chosen = pit.pit_select_and_run_gemm(cands, num, grid, Xts[0], W, M, N, K, out=C, ws=wsel)[1]
+    sec_sel = _time_steps(lambda i: pit.pit_select_and_run_gemm(cands, num, grid, Xts[i % pool], W, M, N, K, out=C, ws=wsel),
+                          steps, warmup)
     X = Xts[0].t().contiguous()
     for _ in range(3):
         torch.matmul(X, W)
@@ -222,7 +263,53 @@ def bench_relu_ffn_correlated(pit, wl, steps, warmup, pool=4):
         torch.matmul(X, W)
     e[1].record()
     torch.cuda.synchronize()
-    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 10}
+    names = ["gather_k_128", "gather_k_64", "gather_k_32", "dense_k"]
+    return {"sec_per_step": by_mt[128], "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 10,
+            "extra": {"ms_per_step_by_tile_height": {str(k): round(v * 1e3, 4) for k, v in by_mt.items()},
+                      "algorithm1_selected": names[chosen], "ms_per_step_selected": round(sec_sel * 1e3, 4)}}
+
+
+def _gather_k_candidates(pit):
+    """Algorithm 1's candidates for a K-major sparse operand: GATHER_K at tile heights 128, 64, 32 and the dense
+    kernel, with the costs of the committed offline profile of this GPU type."""
+    here = os.path.dirname(os.path.abspath(pit.__file__))
+    prof = json.load(open(os.path.join(here, "tile_cost_mi355x.json")))["candidates"]
+    out = []
+    for name, mt, dense in (("gather_k", 128, False), ("gather_k_64", 64, False), ("gather_k_32", 32, False), ("dense_k", 128, True)):
+        out.append({"mt_rows": 1, "mt_cols": mt, "tile_cost": prof[name]["step_ns_per_tile"],
+                    "fixed_cost": prof[name]["step_fixed_ns"], "dense": dense})
+    return out
+
+
+def bench_sweep_4096(pit, wl, steps, warmup):
+    """Three points of the paper's 4096^3 micro-benchmark (Section 5.3; the full sweep is bench_micro.py): zeros in
+    blocks of g tokens x 1 channel of the K-major operand; the step is Algorithm 1's choice run through
+    pit_select_and_run_gemm (index build included for a sparse choice) against hipBLASLt's dense GEMM."""
+    import numpy as np
+    import torch
+    n = 4096
+    g = np.random.default_rng(0)
+    vals = g.standard_normal((n, n)).astype(np.float32)
+    B = _to_dev(wl.to_bf16_bits(g.standard_normal((n, n)).astype(np.float32)))
+    cands = _gather_k_candidates(pit)
+    names = ["gather_k_128", "gather_k_64", "gather_k_32", "dense_k"]
+    C = torch.empty((n, n), dtype=torch.float32, device="cuda")
+    wsel = torch.empty(pit.pit_select_and_run_gemm_workspace(n, n), dtype=torch.uint8, device="cuda")
+    Ad = _to_dev(wl.to_bf16_bits(vals))
+    dense_s = _group_time(lambda: torch.matmul(Ad, B), 2, 8)
+    pts = []
+    for gm, sp in ((32, 0.5), (32, 0.95), (128, 0.9)):
+        keep = wl.iid_block_mask(n, n, 1, gm, sp, seed=int(sp * 100) + gm)
+        At = _to_dev(wl.to_bf16_bits(vals * keep))
+        num = [[int(pit.pit_cover_count(At, 1, c["mt_cols"]).item()) for c in cands]]
+        grid = [[n * (n // c["mt_cols"]) for c in cands]]
+        chosen = pit.pit_select_and_run_gemm(cands, num, grid, At, B, n, n, n, out=C, ws=wsel)[1]
+        sec = _time_steps(lambda i: pit.pit_select_and_run_gemm(cands, num, grid, At, B, n, n, n, out=C, ws=wsel), steps, warmup)
+        nz32 = int((keep.reshape(n, n // 32, 32) != 0).any(axis=2).sum())
+        pts.append({"granularity_tokens": gm, "sparsity": sp, "selected": names[chosen], "ms_per_step": round(sec * 1e3, 4),
+                    "effective_tflops": round(2.0 * nz32 * 32 * n / sec / 1e12, 2),
+                    "speedup_vs_dense": round(dense_s / sec, 3)})
+    return {"dense_ms": round(dense_s * 1e3, 4), "points": pts}
 
 
 def bench_relu_producer(pit, wl, steps, warmup, pool=4):
@@ -298,8 +385,13 @@ def bench_padded_linear(pit, wl, steps, warmup, pool=4):
         torch.matmul(X, W)
     e[1].record()
     torch.cuda.synchronize()
+    # the product kernel alone on the last index (no index build, no clearing of the padding rows)
+    rows = int(ws[(warmup + steps - 1) % pool].lengths.sum())
+    k_s = _group_time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Y, zero_uncovered=False))
     return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 10, "dense_flops": 2.0 * M * K * N,
-            "extra": {"padding_rows_left_untouched_ms_per_step": round(sec_nz * 1e3, 4)}}
+            "extra": {"padding_rows_left_untouched_ms_per_step": round(sec_nz * 1e3, 4), "gemm_kernel_ms": round(k_s * 1e3, 4),
+                      "dense_comparator": "hipBLASLt bf16 GEMM over all 16384 rows, bf16 output (this path: fp32 output, padding rows cleared)",
+                      "roofline": _roofline("mfma", 2.0 * rows * K * N / k_s / 1e12, "k_gather_m_lds (bf16, fp32 C)")}}
 
 
 def bench_microtile(pit, wl, steps, warmup, pool=8):
@@ -329,7 +421,13 @@ def bench_microtile(pit, wl, steps, warmup, pool=8):
         torch.matmul(As[0], B)
     e[1].record()
     torch.cuda.synchronize()
-    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 20, "dense_flops": 2.0 * M * K * N}
+    # the strip kernel alone; its algorithmic bytes: the kept micro-tiles of A, B and C once each (a launch of
+    # this size is bound by launch and first-load latency, not by any throughput)
+    k_s = _group_time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, As[0], B, ix, 32, M, N, K, out=C))
+    alg_bytes = float(ws[0].keep.sum()) * 64 + K * N * 2 + M * N * 4
+    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 20, "dense_flops": 2.0 * M * K * N,
+            "extra": {"gemm_kernel_ms": round(k_s * 1e3, 4),
+                      "roofline": _roofline("hbm", alg_bytes / k_s / 1e9, "k_slab_strip (f16)", "latency-bound at this size: three dependent launches of 3-14 us")}}
 
 
 def bench_moe(pit, wl, steps, warmup, pool=4):
@@ -362,8 +460,15 @@ def bench_moe(pit, wl, steps, warmup, pool=4):
     e[1].record()
     torch.cuda.synchronize()
     weight_bytes = 2.0 * (W1.numel() + W2.numel())
+    # a dense FFN with the same FLOPs: all T tokens through ONE expert's weights (what the layer would cost without routing)
+    Xd = X
+    same_s = _group_time(lambda: torch.matmul(torch.nn.functional.gelu(torch.matmul(Xd, W1[0])), W2[0]), 2, 4)
     return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 5,
-            "dense_flops": 4.0 * E * cap * d_model * d_ff, "hbm_floor_bytes": weight_bytes}
+            "dense_flops": 4.0 * E * cap * d_model * d_ff, "hbm_floor_bytes": weight_bytes,
+            "extra": {"dense_comparator": "capacity-padded batched matmul (every expert padded to the busiest one)",
+                      "dense_ffn_same_flops_one_expert_ms": round(same_s * 1e3, 4),
+                      "roofline": _roofline("hbm", weight_bytes / sec / 1e9, "pit_moe_dispatch_gemm (route index + 2 x k_gather_m_lds)",
+                                            "604 MB of expert weights per pass over the whole call's time")}}
 
 
 def bench_attn(pit, wl, steps, warmup, pool=4):
@@ -392,7 +497,18 @@ def bench_attn(pit, wl, steps, warmup, pool=4):
         torch.softmax(torch.baddbmm(bias, Q, K.transpose(1, 2), alpha=scale).float(), dim=-1).to(torch.bfloat16) @ V
     e[1].record()
     torch.cuda.synchronize()
-    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 5, "dense_flops": 4.0 * H * S * S * D}
+    extra = {"dense_comparator": "unfused torch baddbmm + fp32 softmax + matmul with an additive mask",
+             "gathered_KV_GB_per_s": round(2.0 * H * kept * D * 2 / sec / 1e9, 1),
+             "roofline": _roofline("mfma", eff / sec / 1e12, "pit_sparse_attn (index of the mask + k_sparse_attn)",
+                                   "bound by the gather of K/V rows out of L2 (gathered_KV_GB_per_s) and vector-ALU softmax work, not by the matrix pipe")}
+    try:   # a fused dense comparator, if the library offers one for this mask
+        bm = masks[0].to(torch.bool)
+        f = torch.nn.functional.scaled_dot_product_attention
+        f(Q, K, V, attn_mask=bm, scale=scale)
+        extra["fused_sdpa_dense_ms"] = round(_group_time(lambda: f(Q, K, V, attn_mask=bm, scale=scale), 2, 4) * 1e3, 4)
+    except Exception as ex:
+        extra["fused_sdpa_dense_ms"] = f"unavailable: {type(ex).__name__}"
+    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 5, "dense_flops": 4.0 * H * S * S * D, "extra": extra}
 
 
 def _summary(r):
@@ -441,6 +557,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     side = [("relu_ffn_correlated_zeros", bench_relu_ffn_correlated),
+            ("relu_ffn_dead_runs_of_32_tokens", lambda p_, w_, k_, u_: bench_relu_ffn_correlated(p_, w_, k_, u_, live_block=32)),
+            ("relu_ffn_dead_runs_of_128_at_offset_64", lambda p_, w_, k_, u_: bench_relu_ffn_correlated(p_, w_, k_, u_, live_offset=64)),
             ("relu_ffn_from_preactivation", bench_relu_producer),
             ("microtile_1x32_1024", bench_microtile), ("moe_switch_4096x64", bench_moe),
             ("padded_batch_32x512", bench_padded_linear), ("sparse_attn_4096x12x64", bench_attn)]
@@ -477,7 +595,8 @@ def main():
         "index_share_of_step": round(r["index_ms"] / (r["index_ms"] + r["gemm_ms"]), 4),
         "roofline": {"bound": "mfma", "kernel": "k_gather_k_direct (bf16)", "achieved": round(gemm_tflops, 2),
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / MFMA_PEAK_TFLOPS, 4),
-                     "traffic": _read_traffic("k_gather_k_direct_relu_ffn.txt")},
+                     "traffic": _read_traffic("k_gather_k_direct_relu_ffn.txt"),
+                     "traffic_source": "profiles/k_gather_k_direct_relu_ffn.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a committed run, not measured in this run)"},
         "paper_context": "paper reports up to 5.9x (avg 2.43x) over compilers on A100/V100 end-to-end; no TFLOP/s figure",
     }
     if "cpu" in r:
@@ -486,13 +605,15 @@ def main():
         others = {}
         k, w_ = max(5, args.steps // 2), max(2, args.warmup // 2)
         for name, fn in side:
-            if name.startswith("sparse_attn") and not hasattr(pit._lib, "pit_sparse_attn"):
-                continue
             try:
                 others[name] = _summary(fn(pit, wl, k, w_))
             except Exception as ex:  # a failing side workload must not hide the headline number
                 others[name] = {"error": f"{type(ex).__name__}: {ex}"[:200]}
             torch.cuda.empty_cache()
+        try:
+            others["sweep_4096_cubed_3_points"] = bench_sweep_4096(pit, wl, k, w_)
+        except Exception as ex:
+            others["sweep_4096_cubed_3_points"] = {"error": f"{type(ex).__name__}: {ex}"[:200]}
         line["workloads"] = others
     print(json.dumps(line))
 

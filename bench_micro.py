@@ -1,22 +1,35 @@
 #!/usr/bin/env python3
-"""Synthetic versions of the paper's micro-benchmarks (Section 5.4): a 4096^3 product under block
-sparsity of several granularities and ratios, the index build alone on 4096 x 4096 masks, and the
-overhead at 0 % sparsity.  Prints one JSON object; not part of the bench.py contract.
+"""Synthetic versions of the paper's micro-benchmarks on one MI355X (not part of the bench.py contract).
 
-    python bench_micro.py [--reps 20]
+  * Section 5.3 ("Effectiveness of PIT transformation"): a 4096^3 product whose sparse operand has zeros in
+    blocks of several granularities at 0 - 99 % sparsity, 0 % being the overhead check against the dense kernel.
+    Every kernel the library offers for a K-major operand is timed at every point -- GATHER_K at tile heights
+    128, 64 and 32 (index rebuilt in every step) and the dense kernel -- next to hipBLASLt's dense GEMM, and
+    Algorithm 1 (Section 3.2) is run on the point with the profiled tile costs: its choice is reported beside
+    the measured-fastest kernel.
+  * Section 5.5 / Table 3: granularities 2 x 1, 4 x 1, 8 x 1 and 32 x 1 at 95 % and 99 %, covered by the micro-tiles
+    the kernels offer (32 x 1, 64 x 1, 128 x 1; the paper's CUDA-core tiles go down to 8 x 1).
+  * Section 5.4 ("Sparsity detection"): the index build alone on 4096 x 4096 byte masks.
+
+    python bench_micro.py [--reps 20] [--table]      (--table: a text table instead of JSON)
 """
 import argparse
 import json
+import os
 import sys
+import time
 
 import numpy as np
 import torch
+
+MTS = (128, 64, 32)
 
 
 def _time(fn, reps):
     for _ in range(3):
         fn()
     torch.cuda.synchronize()
+    time.sleep(0.02)          # every measurement starts from the same idle state of the clocks
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
@@ -26,9 +39,54 @@ def _time(fn, reps):
     return e0.elapsed_time(e1) / reps * 1e-3
 
 
+def candidates(pit):
+    """The (dense tile, PIT-axis) pairs of the GATHER_K family with the profiled cost of a step per covered
+    micro-tile and its constant part (committed profile of this GPU type), and the dense kernel."""
+    here = os.path.dirname(os.path.abspath(pit.__file__))
+    prof = json.load(open(os.path.join(here, "tile_cost_mi355x.json")))["candidates"]
+    names = {128: "gather_k", 64: "gather_k_64", 32: "gather_k_32"}
+    c = [{"mt_rows": 1, "mt_cols": mt, "tile_cost": prof[names[mt]]["step_ns_per_tile"],
+          "fixed_cost": prof[names[mt]]["step_fixed_ns"]} for mt in MTS]
+    c.append({"mt_rows": 1, "mt_cols": 128, "tile_cost": prof["dense_k"]["step_ns_per_tile"],
+              "fixed_cost": prof["dense_k"]["step_fixed_ns"], "dense": True})
+    return c
+
+
+def sweep_point(pit, At, B, n, reps, cands, t_dense_lib):
+    """All kernels on one sparse operand At [K, M] (K-major); returns the record of the point."""
+    C = torch.empty((n, n), dtype=torch.float32, device="cuda")
+    rec = {"kernels": {}}
+    for mt in MTS:
+        ix = pit.PitIndex.empty(n // mt, (n // mt) * n)
+        ws = torch.empty(pit.pit_build_index_workspace(n, n, 1, mt, 0), dtype=torch.uint8, device="cuda")
+
+        def step():
+            pit.pit_build_index(At, 1, mt, 0, out=ix, ws=ws)
+            pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, At, B, ix, mt, n, n, n, out=C)
+
+        t = _time(step, reps)
+        t_idx = _time(lambda: pit.pit_build_index(At, 1, mt, 0, out=ix, ws=ws), reps)
+        cover = int(ix.seg_ptr[-1].item()) / float((n // mt) * n)
+        rec["kernels"][f"gather_k_{mt}"] = {"cover": round(cover, 4), "step_us": round(t * 1e6, 1), "index_us": round(t_idx * 1e6, 1)}
+    t = _time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_DENSE_K, At, B, None, 128, n, n, n, out=C), reps)
+    rec["kernels"]["dense_k"] = {"cover": 1.0, "step_us": round(t * 1e6, 1), "index_us": 0.0}
+    # Algorithm 1 on this point: CoverAlgo on the GPU, costs from the profile
+    num = [[int(pit.pit_cover_count(At, 1, c["mt_cols"]).item()) for c in cands]]
+    grid = [[n * (n // c["mt_cols"]) for c in cands]]
+    chosen, _ = pit.pit_select_kernel(cands, num, grid)
+    order = [f"gather_k_{mt}" for mt in MTS] + ["dense_k"]
+    fastest = min(order, key=lambda k: rec["kernels"][k]["step_us"])
+    rec["selected"] = order[chosen]
+    rec["fastest"] = fastest
+    rec["selected_over_fastest"] = round(rec["kernels"][order[chosen]]["step_us"] / rec["kernels"][fastest]["step_us"], 3)
+    rec["speedup_vs_hipblaslt_selected"] = round(t_dense_lib * 1e6 / rec["kernels"][order[chosen]]["step_us"], 3)
+    return rec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--table", action="store_true")
     a = ap.parse_args()
     if not torch.cuda.is_available():
         print("bench_micro.py: no GPU visible", file=sys.stderr)
@@ -43,49 +101,52 @@ def main():
     B = bf16(g.standard_normal((n, n)).astype(np.float32))
     dense_A = bf16(g.standard_normal((n, n)).astype(np.float32))
     t_dense = _time(lambda: torch.matmul(dense_A, B), a.reps)
-    out = {"shape": [n, n, n], "dense_hipblaslt_ms": round(t_dense * 1e3, 4), "gemm": [], "index_build": []}
+    cands = candidates(pit)
+    out = {"shape": [n, n, n], "dense_hipblaslt_us": round(t_dense * 1e6, 1), "gemm": [], "table3": [], "index_build": []}
 
-    # A stored K-major (At[k][m]); sparsity in blocks of gm tokens x gk channels, i.e. At blocks of gk x gm
+    # Section 5.3: A stored K-major (At[k][m]); zeros in blocks of gm tokens x gk channels, i.e. At blocks of gk x gm
     vals = g.standard_normal((n, n)).astype(np.float32)
-    # (64, 32) is also the case of weights pruned in blocks of 32 k x 64 outputs, with the operand roles swapped
-    for gm, gk in ((32, 1), (32, 64), (128, 1), (64, 32)):
+    for gm, gk in ((32, 1), (64, 1), (128, 1), (32, 64)):
         for s in (0.0, 0.5, 0.9, 0.95, 0.99):
             keep = wl.iid_block_mask(n, n, gk, gm, s, seed=int(s * 100) + gm + gk)
-            At = bf16(vals * keep)
-            ix = pit.PitIndex.empty(n // 128, (n // 128) * n)
-            ws = torch.empty(pit.pit_build_index_workspace(n, n, 1, 128, 0), dtype=torch.uint8, device="cuda")
-            C = torch.empty((n, n), dtype=torch.float32, device="cuda")
+            rec = sweep_point(pit, bf16(vals * keep), B, n, a.reps, cands, t_dense)
+            out["gemm"].append({"granularity_tokens_x_channels": [gm, gk], "sparsity": s, **rec})
+    # Table 3: fine granularities under the micro-tiles the kernels offer
+    for gm in (2, 4, 8, 32):
+        for s in (0.95, 0.99):
+            keep = wl.iid_block_mask(n, n, 1, gm, s, seed=int(s * 100) + gm)
+            rec = sweep_point(pit, bf16(vals * keep), B, n, a.reps, cands, t_dense)
+            out["table3"].append({"granularity_tokens_x_channels": [gm, 1], "sparsity": s, **rec})
 
-            def step():
-                pit.pit_build_index(At, 1, 128, 0, out=ix, ws=ws)
-                pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, At, B, ix, 128, n, n, n, out=C)
+    # the headline step replayed from a HIP graph (every replay checked against the eager result)
+    keep = wl.iid_block_mask(n, n, 1, 32, 0.9, seed=77)
+    At = bf16(vals * keep)
+    ix = pit.PitIndex.empty(n // 128, (n // 128) * n)
+    ws = torch.empty(pit.pit_build_index_workspace(n, n, 1, 128, 0), dtype=torch.uint8, device="cuda")
+    C = torch.empty((n, n), dtype=torch.float32, device="cuda")
 
-            t = _time(step, a.reps)
-            t_idx = _time(lambda: pit.pit_build_index(At, 1, 128, 0, out=ix, ws=ws), a.reps)
-            torch.cuda.synchronize()
-            want = C.clone()
-            # the same step replayed from a HIP graph: the GPU's time without the host's launch calls
-            # (every replay is checked against the eager result)
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                step()
-            torch.cuda.current_stream().wait_stream(side)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                step()
-            ok = True
-            for _ in range(3):
-                C.fill_(-1.0)
-                graph.replay()
-                torch.cuda.synchronize()
-                ok = ok and bool(torch.equal(C, want))
-            t_graph = _time(graph.replay, a.reps)
-            cover = int(ix.seg_ptr[-1].item()) / float((n // 128) * n)
-            out["gemm"].append({"granularity_tokens_x_channels": [gm, gk], "sparsity": s, "cover_128x1": round(cover, 4),
-                                "step_ms": round(t * 1e3, 4), "index_ms": round(t_idx * 1e3, 4),
-                                "step_graph_ms": round(t_graph * 1e3, 4), "graph_matches_eager": ok,
-                                "speedup_vs_dense": round(t_dense / min(t, t_graph), 3)})
+    def step():
+        pit.pit_build_index(At, 1, 128, 0, out=ix, ws=ws)
+        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, At, B, ix, 128, n, n, n, out=C)
+
+    t_eager = _time(step, a.reps)
+    want = C.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    ok = True
+    for _ in range(3):
+        C.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        ok = ok and bool(torch.equal(C, want))
+    out["graph_replay"] = {"point": "32x1 at 90 %, mt 128", "eager_us": round(t_eager * 1e6, 1),
+                           "graph_us": round(_time(graph.replay, a.reps) * 1e6, 1), "graph_matches_eager": ok}
 
     # A row-major [m][k], zeros in blocks of 1 token x 64 channels: PIT-axis m inside k-slabs of 64
     # (GATHER_M, the slabs' partial products are added in strips of C held in LDS)
@@ -95,27 +156,42 @@ def main():
         A = bf16(vals * keep)
         ix = pit.PitIndex.empty(n // 64, (n // 64) * n)
         ws = torch.empty(pit.pit_build_index_workspace(n, n, 1, 64, 0), dtype=torch.uint8, device="cuda")
-        C = torch.empty((n, n), dtype=torch.float32, device="cuda")
 
         def step_m():
             pit.pit_build_index(A, 1, 64, 0, out=ix, ws=ws)
             pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, A, B, ix, 64, n, n, n, out=C)
 
         t = _time(step_m, a.reps)
-        torch.cuda.synchronize()
         cover = int(ix.seg_ptr[-1].item()) / float((n // 64) * n)
-        out["gemm_row_major_1x64"].append({"sparsity": s, "cover_1x64": round(cover, 4), "step_ms": round(t * 1e3, 4),
-                                           "speedup_vs_dense": round(t_dense / t, 3)})
+        out["gemm_row_major_1x64"].append({"sparsity": s, "cover_1x64": round(cover, 4), "step_us": round(t * 1e6, 1),
+                                           "speedup_vs_hipblaslt": round(t_dense / t, 3)})
 
-    # index build alone on byte masks (Section 5.4, "Sparsity detection"), 99 % sparsity
+    # Section 5.4: index build alone on byte masks, 99 % sparsity
     for gr in (1, 16, 32):
         m = torch.from_numpy(wl.iid_block_mask(n, n, gr, gr, 0.99, seed=gr)).cuda()
         ix = pit.PitIndex.empty(n // gr, (n // gr) * (n // gr))
         ws = torch.empty(pit.pit_build_index_workspace(n, n, gr, gr, 1), dtype=torch.uint8, device="cuda")
         t = _time(lambda: pit.pit_build_index(m, gr, gr, 1, out=ix, ws=ws), a.reps)
-        out["index_build"].append({"mask": [n, n], "micro_tile": [gr, gr], "ms": round(t * 1e3, 4),
+        out["index_build"].append({"mask": [n, n], "micro_tile": [gr, gr], "us": round(t * 1e6, 1),
                                    "GB_per_s": round(n * n / t / 1e9, 1)})
-    print(json.dumps(out))
+    if not a.table:
+        print(json.dumps(out))
+        return
+    print(f"4096^3 bf16, sparse operand K-major; hipBLASLt dense GEMM {out['dense_hipblaslt_us']} us; step = index build + product")
+    print("cover / step us per kernel; sel = Algorithm 1 with the profiled costs; best = measured fastest")
+    hdr = f"{'granularity':>11} {'sparsity':>8} | " + " | ".join(f"{k:>16}" for k in ("gather_k 128", "gather_k 64", "gather_k 32")) + \
+          f" | {'dense_k':>8} | {'sel':>12} {'best':>12} {'sel/best':>8} {'vs lib':>6}"
+    for key, title in (("gemm", "Section 5.3 sweep"), ("table3", "Table 3 granularities")):
+        print("\n" + title + "\n" + hdr)
+        for r in out[key]:
+            k = r["kernels"]
+            gm, gk = r["granularity_tokens_x_channels"]
+            cells = " | ".join(f"{k[f'gather_k_{mt}']['cover']:>6.3f} {k[f'gather_k_{mt}']['step_us']:>8.1f}" + " " for mt in MTS)
+            print(f"{gm:>7}x{gk:<3} {r['sparsity']:>8} | {cells} | {k['dense_k']['step_us']:>8.1f} | {r['selected']:>12} {r['fastest']:>12} "
+                  f"{r['selected_over_fastest']:>8} {r['speedup_vs_hipblaslt_selected']:>6}")
+    print("\ngraph replay:", out["graph_replay"])
+    print("row-major operand, zeros 1 x 64 (GATHER_M k-slabs):", out["gemm_row_major_1x64"])
+    print("index build alone (Section 5.4), byte masks at 99 %:", out["index_build"])
 
 
 if __name__ == "__main__":

@@ -176,6 +176,9 @@ typedef struct pit_kernel_candidate {
   int32_t mt_rows, mt_cols;
   int32_t dense;       /* 0 = sparse kernel, 1 = dense kernel */
   double  tile_cost;
+  double  fixed_cost;  /* cost of one run that does not depend on the number of micro-tiles (launches, index
+                          build, set-up and stores of the output), same unit as tile_cost; 0 gives the
+                          paper's formula exactly (Algorithm 1: CoverAlgo x tile_cost) */
 } pit_kernel_candidate;
 
 /*
@@ -185,9 +188,12 @@ typedef struct pit_kernel_candidate {
  *              read back from pit_cover_count; ignored for dense candidates
  *   grid_tiles [nsamples x ncand] (host): number of micro-tiles of candidate j in sample i's whole
  *              grid (rows/mt_rows * cols/mt_cols); used for dense candidates
- *   cost_out   [ncand] (host) or NULL: receives sum over samples of tiles * tile_cost
+ *   cost_out   [ncand] (host) or NULL: receives sum over samples of (fixed_cost + tiles * tile_cost)
  *   best_out   receives the index of the cheapest candidate, the first one among equals
  * Errors: PIT_EINVAL (NULL pointers, ncand <= 0, nsamples < 0, negative counts or costs).
+ * The fixed term is this library's addition to the paper's cost model: on this GPU a step of a few
+ * tens of microseconds has a constant part (two or three launches, the output's stores) that a purely
+ * proportional model charges to no one; the offline profile measures it with the tile cost.
  */
 int pit_select_kernel(const pit_kernel_candidate* cand, int ncand, const int64_t* num_tiles,
                       const int64_t* grid_tiles, int nsamples, double* cost_out, int* best_out);
@@ -223,7 +229,13 @@ typedef enum pit_gemm_mode {
    * ratio after cover") -- and reads B once per mt rows of C instead of once per 128; which one is
    * cheaper for given data is what pit_select_kernel decides.
    */
-  PIT_GEMM_GATHER_K = 1
+  PIT_GEMM_GATHER_K = 1,
+  /*
+   * The dense kernel Algorithm 1 falls back to at low sparsity (paper Section 3.2): the GATHER_K tile
+   * (A supplied K-major, mt = tile height 128, 64 or 32) with identity addressing -- every k is
+   * multiplied, no index is built or read; ix is ignored and may be NULL.
+   */
+  PIT_GEMM_DENSE_K = 2
 } pit_gemm_mode;
 
 /*
@@ -232,12 +244,37 @@ typedef enum pit_gemm_mode {
  *          fp32 accumulator, nearest-even; not available when nseg > 1 in GATHER_M mode).
  *   ix     index built by pit_build_index on A (or on a row mask) with the micro-tile named above.
  * Shape rules (else PIT_ESHAPE): N % 128 == 0; GATHER_M: mt % 32 == 0 and K % mt == 0;
- * GATHER_K: mt in {32, 64, 128}, M % mt == 0.  Pointers 16-byte aligned, leading dimensions % 8 == 0.
+ * GATHER_K and DENSE_K: mt in {32, 64, 128}, M % mt == 0.  Pointers 16-byte aligned, leading dimensions % 8 == 0.
  * Index entries outside the valid coordinate range are a caller error (not checked on the device).
  */
 int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void* d_B, int64_t ldb,
                    void* d_C, int64_t ldc, int M, int N, int K, int in_dt, int c_dt,
                    const pit_index* ix, int mt, int zero_uncovered, pit_stream stream);
+
+/* Bytes of device workspace pit_select_and_run_gemm needs (0 on invalid arguments). */
+size_t pit_select_and_run_gemm_workspace(int M, int K);
+
+/*
+ * Algorithm 1 (paper Section 3.2) followed by the kernel it selects, for C[M x N] = A . B with A
+ * supplied K-major (d_At is [K x M] row-major, m contiguous).
+ * Selection (host, as pit_select_kernel): cand / num_tiles / grid_tiles / nsamples describe the
+ * (dense tile, PIT-axis) pairs to choose from and CoverAlgo's counts on the caller's sparsity
+ * samples (e.g. from pit_cover_count on earlier activations).  A sparse candidate must have
+ * mt_rows == 1 and mt_cols in {32, 64, 128} (micro-tiles of mt_cols consecutive m of one k: the tile
+ * heights the GATHER_K kernel offers); a dense candidate stands for PIT_GEMM_DENSE_K at tile height
+ * mt_cols.  nsamples == 0 selects candidate 0.
+ * Run (device, on `stream`): a sparse winner builds the index of d_At at its micro-tile in the
+ * workspace (pit_build_index) and launches pit_sread_gemm(PIT_GEMM_GATHER_K) at that tile height; a
+ * dense winner launches PIT_GEMM_DENSE_K.  *chosen (host, may be NULL) receives the winner's index.
+ *   d_ws  at least pit_select_and_run_gemm_workspace(M, K) bytes, 256-byte aligned.
+ * Errors: as pit_select_kernel, pit_build_index and pit_sread_gemm; PIT_ESHAPE if a candidate's
+ * micro-tile is not one the kernels offer or M is not a multiple of it.
+ */
+int pit_select_and_run_gemm(const pit_kernel_candidate* cand, int ncand, const int64_t* num_tiles,
+                            const int64_t* grid_tiles, int nsamples,
+                            const void* d_At, int64_t lda, const void* d_B, int64_t ldb,
+                            void* d_C, int64_t ldc, int M, int N, int K, int in_dt, int c_dt,
+                            void* d_ws, size_t ws_bytes, int* chosen, pit_stream stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Mixture of experts (paper Section 2.1 "Mixture-of-Experts", Section 5.1 "Switch Transformer"):

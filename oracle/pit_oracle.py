@@ -174,7 +174,10 @@ def select_kernel(samples, candidates):
     processes every micro-tile of the grid whatever the data, which is how low sparsity falls back
     to dense computation.  For every candidate the cost is the sum over the sparsity samples of
     CoverAlgo(sample, micro-tile) * tile_cost; the result is (index of the cheapest candidate, the
-    first one among equals; list of all costs).  parity pinned in tests/test_oracle_select.py."""
+    first one among equals; list of all costs).  An optional ``fixed_cost`` per candidate (default 0,
+    which is the paper's formula) is added once per sample: a reading that goes beyond the paper, for
+    hardware where a run has a constant part next to the part proportional to the tiles.
+    parity pinned in tests/test_oracle_select.py."""
     best, best_cost, costs = -1, math.inf, []
     for i, c in enumerate(candidates):
         cost = 0.0
@@ -184,7 +187,7 @@ def select_kernel(samples, candidates):
                 num_tiles = (rows // c["mt_rows"]) * (cols // c["mt_cols"])
             else:
                 num_tiles = cover_count(D, c["mt_rows"], c["mt_cols"])
-            cost += num_tiles * c["tile_cost"]
+            cost += c.get("fixed_cost", 0.0) + num_tiles * c["tile_cost"]
         costs.append(cost)
         if cost < best_cost:
             best, best_cost = i, cost

@@ -17,6 +17,8 @@
 #include "pit_gemm.hpp"
 #include "pit_gemm_dev.hpp"
 #include <type_traits>
+#include <algorithm>
+#include <climits>
 
 namespace pit {
 namespace {
@@ -179,6 +181,7 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
   const int tn = g.N / TN, total = tn * tm_tiles;
   // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that each
   // XCD works on a contiguous run of tiles, ordered in bands of 4 tile rows x all tile columns.
+  const bool dense = g.idx == nullptr;
   auto tile_of = [&](int lin) -> DirectTile {
     const int x = lin & 7, qq = total >> 3, rr = total & 7;
     const int lp = x * qq + min(x, rr) + (lin >> 3);
@@ -188,8 +191,9 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
     DirectTile t;
     t.seg = band * GM + within % rows;
     t.n0 = (within / rows) * TN;
-    const int list_begin = g.seg_ptr[t.seg];
-    t.list_len = g.seg_ptr[t.seg + 1] - list_begin;
+    // dense mode (no index): every tile's list is 0, 1, .., K - 1 and is never read from memory
+    const int list_begin = dense ? 0 : g.seg_ptr[t.seg];
+    t.list_len = dense ? g.K : g.seg_ptr[t.seg + 1] - list_begin;
     const int nslab = (t.list_len + SK - 1) / SK;
     t.n_w = nslab > wv ? (nslab - wv + NW - 1) / NW : 0;   // this wave's slabs: wv, wv + NW, ...
     t.list = uniform_ptr(g.idx + list_begin);
@@ -201,6 +205,7 @@ k_gather_k_direct(const GemmArgs g, const int tm_tiles) {
   // lane l of a slab's list load holds entry (l % 32) of the slab
   auto load_list = [&](const DirectTile& T, int t) -> int {
     const int pos = min(SK * (wv + NW * t) + (lane & 31), T.list_len - 1);
+    if (dense) return pos;
     typedef const int __attribute__((address_space(1))) * gint_t;
     return *(gint_t)(uintptr_t)(reinterpret_cast<uintptr_t>(T.list) + (uint32_t)pos * 4u);
   };
@@ -729,10 +734,10 @@ using namespace pit;
 extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void* d_B, int64_t ldb,
                               void* d_C, int64_t ldc, int M, int N, int K, int in_dt, int c_dt,
                               const pit_index* ix, int mt, int zero_uncovered, pit_stream stream) {
-  if (!ix || !ix->seg_ptr) return PIT_EINVAL;
+  if (mode != PIT_GEMM_GATHER_M && mode != PIT_GEMM_GATHER_K && mode != PIT_GEMM_DENSE_K) return PIT_EINVAL;
+  if (mode != PIT_GEMM_DENSE_K && (!ix || !ix->seg_ptr)) return PIT_EINVAL;
   if (in_dt != PIT_BF16 && in_dt != PIT_F16) return PIT_EINVAL;
   if (c_dt != PIT_F32 && c_dt != in_dt) return PIT_EINVAL;
-  if (mode != PIT_GEMM_GATHER_M && mode != PIT_GEMM_GATHER_K) return PIT_EINVAL;
   if (M < 0 || N < 0 || K < 0 || mt <= 0) return PIT_ESHAPE;
   if (N % TN) return PIT_ESHAPE;
   const int c_esize = c_dt == PIT_F32 ? 4 : 2;
@@ -740,14 +745,22 @@ extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void
   if (M == 0 || N == 0) return PIT_OK;
   if (!d_C || !aligned(d_C, 16) || ldc < N || (ldc * c_esize) % 16) return PIT_EINVAL;
   if (K > 0) {
-    if (!d_A || !d_B || !ix->idx) return PIT_EINVAL;
+    if (!d_A || !d_B || (mode != PIT_GEMM_DENSE_K && !ix->idx)) return PIT_EINVAL;
     if (!aligned(d_A, 16) || !aligned(d_B, 16) || lda % 8 || ldb % 8 || ldb < N) return PIT_EINVAL;
   }
 
   GemmArgs g = {};
   g.A = d_A; g.lda = lda; g.B = d_B; g.ldb = ldb; g.b_seg_stride = 0;
-  g.C = d_C; g.ldc = ldc; g.seg_ptr = ix->seg_ptr; g.idx = ix->idx; g.gate = nullptr;
-  g.nseg = ix->nseg; g.M = M; g.N = N; g.K = K;
+  g.C = d_C; g.ldc = ldc; g.gate = nullptr;
+  g.M = M; g.N = N; g.K = K;
+  if (mode == PIT_GEMM_DENSE_K) {
+    // the dense kernel of Algorithm 1's fallback: the GATHER_K tile with identity addressing
+    if ((mt != 128 && mt != 64 && mt != 32) || M % mt) return PIT_ESHAPE;
+    if (K > 0 && lda < M) return PIT_EINVAL;
+    g.seg_ptr = nullptr; g.idx = nullptr; g.nseg = M / mt; g.slab = mt;
+    return launch_sread_gemm_k(in_dt == PIT_BF16, c_dt != PIT_F32, g, M / mt, st);
+  }
+  g.seg_ptr = ix->seg_ptr; g.idx = ix->idx; g.nseg = ix->nseg;
 
   if (mode == PIT_GEMM_GATHER_K) {
     if ((mt != 128 && mt != 64 && mt != 32) || M % mt) return PIT_ESHAPE;
@@ -790,4 +803,67 @@ extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void
   else                   hipLaunchKernelGGL((k_slab_strip<false, CW>), grid, dim3(256), 0, st, g);
   PIT_LAUNCH_CHECK();
   return PIT_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Algorithm 1 end to end: select among the GATHER_K tile heights and the dense kernel, then run the winner.
+// ------------------------------------------------------------------------------------------------
+namespace pit {
+namespace {
+struct SelectWs { size_t seg_ptr_off, idx_off, build_off, total; };
+// sized for the finest micro-tile (32): the most segments and the most entries
+SelectWs select_layout(int M, int K) {
+  SelectWs w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) & ~(size_t)255; return at; };
+  const size_t nseg = (size_t)(M > 0 ? M : 0) / 32 + 1;
+  w.seg_ptr_off = take((nseg + 1) * 4);
+  w.idx_off = take((nseg * (size_t)(K > 0 ? K : 1)) * 4);
+  size_t b = 0;
+  for (int mt : {32, 64, 128}) b = std::max(b, pit_build_index_workspace(K, M - M % mt, 1, mt, 0, 0));
+  w.build_off = take(b + 64);
+  w.total = o;
+  return w;
+}
+}  // namespace
+}  // namespace pit
+
+extern "C" size_t pit_select_and_run_gemm_workspace(int M, int K) {
+  if (M < 0 || K < 0) return 0;
+  return select_layout(M, K).total;
+}
+
+extern "C" int pit_select_and_run_gemm(const pit_kernel_candidate* cand, int ncand, const int64_t* num_tiles,
+                                       const int64_t* grid_tiles, int nsamples,
+                                       const void* d_At, int64_t lda, const void* d_B, int64_t ldb,
+                                       void* d_C, int64_t ldc, int M, int N, int K, int in_dt, int c_dt,
+                                       void* d_ws, size_t ws_bytes, int* chosen, pit_stream stream) {
+  if (!cand || ncand <= 0) return PIT_EINVAL;
+  for (int j = 0; j < ncand; ++j) {
+    const int mt = cand[j].mt_cols;
+    if (cand[j].mt_rows != 1 || (mt != 32 && mt != 64 && mt != 128)) return PIT_ESHAPE;
+  }
+  int best = 0;
+  const int rc = pit_select_kernel(cand, ncand, num_tiles, grid_tiles, nsamples, nullptr, &best);
+  if (rc != PIT_OK) return rc;
+  if (chosen) *chosen = best;
+  const int mt = cand[best].mt_cols;
+  if (M < 0 || N < 0 || K < 0) return PIT_ESHAPE;
+  if (M % mt) return PIT_ESHAPE;
+  if (cand[best].dense)
+    return pit_sread_gemm(PIT_GEMM_DENSE_K, d_At, lda, d_B, ldb, d_C, ldc, M, N, K, in_dt, c_dt, nullptr, mt, 0, stream);
+  const SelectWs L = select_layout(M, K);
+  if (!d_ws || !aligned(d_ws, 256)) return PIT_EINVAL;
+  if (ws_bytes < L.total) return PIT_ECAPACITY;
+  char* ws = reinterpret_cast<char*>(d_ws);
+  pit_index ix;
+  ix.seg_ptr = reinterpret_cast<int32_t*>(ws + L.seg_ptr_off);
+  ix.idx = reinterpret_cast<int32_t*>(ws + L.idx_off);
+  ix.bits = nullptr;
+  ix.nseg = M / mt;
+  ix.cap = (int32_t)std::min<int64_t>((int64_t)(M / mt) * K, INT32_MAX);
+  if ((int64_t)(M / mt) * K > INT32_MAX) return PIT_ESHAPE;
+  const int rb = pit_build_index(d_At, in_dt, K, M, lda, 1, mt, 0, &ix, ws + L.build_off, L.total - L.build_off, stream);
+  if (rb != PIT_OK) return rb;
+  return pit_sread_gemm(PIT_GEMM_GATHER_K, d_At, lda, d_B, ldb, d_C, ldc, M, N, K, in_dt, c_dt, &ix, mt, 0, stream);
 }

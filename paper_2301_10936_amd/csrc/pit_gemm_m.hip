@@ -325,7 +325,11 @@ int launch_cfg(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
 // mixture-of-experts call 209-211, 240-271 (rows of small experts are padded to 256) and 194-202 us.)
 template <bool BF, int EPI, int CT>
 int launch_shape(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
-  if (g.N % 256 == 0) return launch_cfg<BF, EPI, CT, 2, 4, 3>(g, total_rows, st);
+  // (a product too small to give every compute unit a 128 x 256 tile even in the worst case takes 128 x 128)
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+  const int64_t wide_tiles = (total_rows / 128 + g.nseg) * (g.N / 256);
+  if (g.N % 256 == 0 && wide_tiles >= cus) return launch_cfg<BF, EPI, CT, 2, 4, 3>(g, total_rows, st);
   return launch_cfg<BF, EPI, CT, 2, 2, 4>(g, total_rows, st);
 }
 

@@ -1020,12 +1020,12 @@ extern "C" int pit_select_kernel(const pit_kernel_candidate* cand, int ncand, co
   int best = -1;
   double best_cost = 0.0;
   for (int j = 0; j < ncand; ++j) {
-    if (!(cand[j].tile_cost >= 0.0) || cand[j].mt_rows <= 0 || cand[j].mt_cols <= 0) return PIT_EINVAL;
+    if (!(cand[j].tile_cost >= 0.0) || !(cand[j].fixed_cost >= 0.0) || cand[j].mt_rows <= 0 || cand[j].mt_cols <= 0) return PIT_EINVAL;
     double cost = 0.0;
     for (int i = 0; i < nsamples; ++i) {
       const int64_t n = cand[j].dense ? grid_tiles[(int64_t)i * ncand + j] : num_tiles[(int64_t)i * ncand + j];
       if (n < 0) return PIT_EINVAL;
-      cost += (double)n * cand[j].tile_cost;
+      cost += cand[j].fixed_cost + (double)n * cand[j].tile_cost;
     }
     if (cost_out) cost_out[j] = cost;
     if (best < 0 || cost < best_cost) { best = j; best_cost = cost; }

@@ -20,7 +20,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 
 PIT_OK, PIT_EINVAL, PIT_ESHAPE, PIT_ECAPACITY, PIT_EHIP = 0, -1, -2, -3, -4
 PIT_U8, PIT_F16, PIT_BF16, PIT_F32 = 0, 1, 2, 3
-PIT_GEMM_GATHER_M, PIT_GEMM_GATHER_K = 0, 1
+PIT_GEMM_GATHER_M, PIT_GEMM_GATHER_K, PIT_GEMM_DENSE_K = 0, 1, 2
 _STATUS = {0: "PIT_OK", -1: "PIT_EINVAL", -2: "PIT_ESHAPE", -3: "PIT_ECAPACITY", -4: "PIT_EHIP"}
 
 EXPORTS = ["pit_last_hip_error", "pit_version", "pit_build_index_workspace", "pit_build_index",
@@ -28,6 +28,7 @@ EXPORTS = ["pit_last_hip_error", "pit_version", "pit_build_index_workspace", "pi
            "pit_build_route_index_workspace", "pit_build_route_index",
            "pit_relu_channel_major_index_workspace", "pit_relu_channel_major_index",
            "pit_cover_count_workspace", "pit_cover_count", "pit_select_kernel", "pit_sread_gemm",
+           "pit_select_and_run_gemm_workspace", "pit_select_and_run_gemm",
            "pit_moe_workspace", "pit_moe_dispatch_gemm", "pit_sparse_attn_workspace", "pit_sparse_attn"]
 
 
@@ -60,7 +61,7 @@ _lib.pit_relu_channel_major_index.argtypes = [c_vp, c_i64, c_int, c_int, c_int, 
 
 class _CCandidate(ctypes.Structure):
     _fields_ = [("mt_rows", ctypes.c_int32), ("mt_cols", ctypes.c_int32), ("dense", ctypes.c_int32),
-                ("tile_cost", ctypes.c_double)]
+                ("tile_cost", ctypes.c_double), ("fixed_cost", ctypes.c_double)]
 
 
 _lib.pit_cover_count_workspace.restype = c_sz
@@ -73,17 +74,22 @@ _lib.pit_select_kernel.argtypes = [ctypes.POINTER(_CCandidate), c_int, ctypes.PO
 _lib.pit_sread_gemm.restype = c_int
 _lib.pit_sread_gemm.argtypes = [c_int, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_int, c_int, c_int, c_int, c_int,
                                 _P, c_int, c_int, c_vp]
+_lib.pit_select_and_run_gemm_workspace.restype = c_sz
+_lib.pit_select_and_run_gemm_workspace.argtypes = [c_int, c_int]
+_lib.pit_select_and_run_gemm.restype = c_int
+_lib.pit_select_and_run_gemm.argtypes = [ctypes.POINTER(_CCandidate), c_int, ctypes.POINTER(c_i64), ctypes.POINTER(c_i64), c_int,
+                                         c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_int, c_int, c_int, c_int, c_int,
+                                         c_vp, c_sz, ctypes.POINTER(c_int), c_vp]
 _lib.pit_moe_workspace.restype = c_sz
 _lib.pit_moe_workspace.argtypes = [c_int] * 4
 _lib.pit_moe_dispatch_gemm.restype = c_int
 _lib.pit_moe_dispatch_gemm.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int,
                                        c_int, c_vp, c_vp, c_sz, c_vp]
-if hasattr(_lib, "pit_sparse_attn"):
-    _lib.pit_sparse_attn_workspace.restype = c_sz
-    _lib.pit_sparse_attn_workspace.argtypes = [c_int] * 3
-    _lib.pit_sparse_attn.restype = c_int
-    _lib.pit_sparse_attn.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_f, c_int,
-                                     c_vp, c_sz, c_vp]
+_lib.pit_sparse_attn_workspace.restype = c_sz
+_lib.pit_sparse_attn_workspace.argtypes = [c_int] * 3
+_lib.pit_sparse_attn.restype = c_int
+_lib.pit_sparse_attn.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_f, c_int,
+                                 c_vp, c_sz, c_vp]
 
 
 class PitError(RuntimeError):
@@ -245,30 +251,66 @@ def pit_cover_count(src: torch.Tensor, mt_rows: int, mt_cols: int, out: torch.Te
 
 
 def pit_select_kernel(candidates, num_tiles, grid_tiles):
-    """Algorithm 1 on the host.  candidates: sequence of dicts (mt_rows, mt_cols, tile_cost, optional dense);
-    num_tiles / grid_tiles: [nsamples][ncand] integers.  Returns (best index, list of costs)."""
-    ncand, nsamples = len(candidates), len(num_tiles)
-    cands = (_CCandidate * max(ncand, 1))()
-    for j, c in enumerate(candidates):
-        cands[j] = _CCandidate(int(c["mt_rows"]), int(c["mt_cols"]), int(bool(c.get("dense", False))), float(c["tile_cost"]))
-    flat_n = (c_i64 * max(ncand * nsamples, 1))(*[int(v) for row in num_tiles for v in row])
-    flat_g = (c_i64 * max(ncand * nsamples, 1))(*[int(v) for row in grid_tiles for v in row])
+    """Algorithm 1 on the host.  candidates: sequence of dicts (mt_rows, mt_cols, tile_cost, optional dense,
+    optional fixed_cost); num_tiles / grid_tiles: [nsamples][ncand] integers.  Returns (best index, list of costs)."""
+    cands, flat_n, flat_g, ncand, nsamples = _candidates(candidates, num_tiles, grid_tiles)
     costs = (ctypes.c_double * max(ncand, 1))()
     best = c_int(-1)
     _check(_lib.pit_select_kernel(cands, ncand, flat_n, flat_g, nsamples, costs, ctypes.byref(best)), "pit_select_kernel")
     return best.value, [costs[j] for j in range(ncand)]
 
 
-def pit_sread_gemm(mode: int, A: torch.Tensor, B: torch.Tensor, ix: PitIndex, mt: int, M: int, N: int, K: int,
+def _check_operands(A: torch.Tensor, B: torch.Tensor, where: str) -> None:
+    if A.dtype != B.dtype or A.dim() != 2 or B.dim() != 2 or (A.numel() and A.stride(1) != 1) or (B.numel() and B.stride(1) != 1):
+        raise PitError(PIT_EINVAL, where + " (operands must be 2-D, of one 16-bit type, last dimension contiguous)")
+
+
+def pit_sread_gemm(mode: int, A: torch.Tensor, B: torch.Tensor, ix: PitIndex | None, mt: int, M: int, N: int, K: int,
                    out: torch.Tensor | None = None, c_dtype=torch.float32, zero_uncovered: bool = True) -> torch.Tensor:
-    """C = A.B over the listed micro-tiles.  GATHER_M: A is [M,K]; GATHER_K: A is At [K,M].  B is [K,N]."""
+    """C = A.B over the listed micro-tiles.  GATHER_M: A is [M,K]; GATHER_K and DENSE_K (ix = None): A is At [K,M].
+    B is [K,N]."""
+    _check_operands(A, B, "pit_sread_gemm")
     if out is None:
         out = torch.empty((M, N), dtype=c_dtype, device=B.device)
-    ci = ix.c()
+    ci = ix.c() if ix is not None else None
     _check(_lib.pit_sread_gemm(mode, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), out.data_ptr(), out.stride(0),
-                               M, N, K, _dt(B), _dt(out), ctypes.byref(ci), mt, int(zero_uncovered), _stream()),
+                               M, N, K, _dt(B), _dt(out), ctypes.byref(ci) if ci is not None else None, mt,
+                               int(zero_uncovered), _stream()),
            "pit_sread_gemm")
     return out
+
+
+def _candidates(candidates, num_tiles, grid_tiles):
+    ncand, nsamples = len(candidates), len(num_tiles)
+    cands = (_CCandidate * max(ncand, 1))()
+    for j, c in enumerate(candidates):
+        cands[j] = _CCandidate(int(c["mt_rows"]), int(c["mt_cols"]), int(bool(c.get("dense", False))), float(c["tile_cost"]),
+                               float(c.get("fixed_cost", 0.0)))
+    flat_n = (c_i64 * max(ncand * nsamples, 1))(*[int(v) for row in num_tiles for v in row])
+    flat_g = (c_i64 * max(ncand * nsamples, 1))(*[int(v) for row in grid_tiles for v in row])
+    return cands, flat_n, flat_g, ncand, nsamples
+
+
+def pit_select_and_run_gemm_workspace(M, K) -> int:
+    return _lib.pit_select_and_run_gemm_workspace(M, K)
+
+
+def pit_select_and_run_gemm(candidates, num_tiles, grid_tiles, At: torch.Tensor, B: torch.Tensor, M: int, N: int, K: int,
+                            out: torch.Tensor | None = None, c_dtype=torch.float32, ws: torch.Tensor | None = None):
+    """Algorithm 1 over `candidates` (as for pit_select_kernel) and the winner's kernel on At [K,M], B [K,N].
+    Returns (C, index of the chosen candidate).  See include/pit.h."""
+    _check_operands(At, B, "pit_select_and_run_gemm")
+    if out is None:
+        out = torch.empty((M, N), dtype=c_dtype, device=B.device)
+    if ws is None:
+        ws = torch.empty(max(pit_select_and_run_gemm_workspace(M, K), 256), dtype=torch.uint8, device=B.device)
+    cands, flat_n, flat_g, ncand, nsamples = _candidates(candidates, num_tiles, grid_tiles)
+    chosen = c_int(-1)
+    _check(_lib.pit_select_and_run_gemm(cands, ncand, flat_n, flat_g, nsamples, At.data_ptr(), At.stride(0), B.data_ptr(),
+                                        B.stride(0), out.data_ptr(), out.stride(0), M, N, K, _dt(B), _dt(out),
+                                        ws.data_ptr(), ws.numel(), ctypes.byref(chosen), _stream()),
+           "pit_select_and_run_gemm")
+    return out, chosen.value
 
 
 def pit_moe_workspace(T, d_model, d_ff, E) -> int:
@@ -279,6 +321,10 @@ def pit_moe_dispatch_gemm(X, expert_id, gate, W1, W2, out=None, y_dtype=torch.fl
                           status=None, ws=None) -> torch.Tensor:
     T, d_model = X.shape
     E, _, d_ff = W1.shape
+    if not (X.dtype == W1.dtype == W2.dtype and X.is_contiguous() and W1.is_contiguous() and W2.is_contiguous()
+            and expert_id.dtype == torch.int32 and expert_id.is_contiguous() and tuple(W2.shape) == (E, d_ff, d_model)
+            and (gate is None or (gate.dtype == torch.float32 and gate.is_contiguous()))):
+        raise PitError(PIT_EINVAL, "pit_moe_dispatch_gemm (contiguous X, W1, W2 of one 16-bit type, int32 expert ids, fp32 gate)")
     if out is None:
         out = torch.empty((T, d_model), dtype=y_dtype, device=X.device)
     if ws is None:
@@ -295,6 +341,10 @@ def pit_sparse_attn_workspace(H, S, D) -> int:
 
 def pit_sparse_attn(Q, K, V, mask, scale: float, out=None, o_dtype=torch.float32, ws=None) -> torch.Tensor:
     H, S, D = Q.shape
+    if not (Q.dtype == K.dtype == V.dtype and Q.is_contiguous() and K.is_contiguous() and V.is_contiguous()
+            and K.shape == Q.shape and V.shape == Q.shape and mask.dtype in (torch.uint8, torch.bool)
+            and mask.is_contiguous() and tuple(mask.shape) == (S, S)):
+        raise PitError(PIT_EINVAL, "pit_sparse_attn (contiguous Q, K, V of one 16-bit type and shape, byte mask [S, S])")
     if out is None:
         out = torch.empty((H, S, D), dtype=o_dtype, device=Q.device)
     if ws is None:

@@ -9,10 +9,17 @@ table as JSON -- the ``tile_cost`` values of pit_select_kernel's candidates.
 
 Candidates (micro-tile shape on A as stored [M, K]):
     gather_k     128 x 1   k is the PIT-axis (A supplied K-major), pit_sread_gemm(GATHER_K, mt=128)
+    gather_k_64  64 x 1    the same with the 64-row tile, mt=64;   gather_k_32  32 x 1, mt=32
+    dense_k      128 x 1   the dense kernel (PIT_GEMM_DENSE_K, identity addressing, no index): cost per
+                           micro-tile of the whole grid
     gather_m_S   1 x S     m is the PIT-axis, k-slabs of S in {32, 64, 128}, pit_sread_gemm(GATHER_M, mt=S)
     gather_m_row 1 x K     m is the PIT-axis, whole rows, pit_sread_gemm(GATHER_M, mt=K)
-The dense kernel is the same tile with every micro-tile listed; its cost per micro-tile is the
-cost measured at full cover.
+"sparse_ns_per_tile" is measured at the stated cover (keep), "dense_ns_per_tile" at full cover through the
+index.  For the gather_k family and the dense kernel, a whole step (pit_build_index at the candidate's
+micro-tile + the product; the dense kernel builds no index) is also fitted as
+    step time = "step_fixed_ns" + covered micro-tiles x "step_ns_per_tile"
+from two covers (0.1 and 0.6) of a 4096^3 product (the dense kernel: from two extents of k): these two numbers
+are the fixed_cost and tile_cost of pit_select_kernel's candidates.
 """
 import argparse
 import json
@@ -33,6 +40,7 @@ def _time(fn, reps=20):
     for _ in range(3):
         fn()
     torch.cuda.synchronize()
+    time.sleep(0.02)          # every measurement starts from the same idle state of the clocks
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
@@ -47,13 +55,13 @@ def measure(M=2048, K=4096, N=2048, keep=0.5, seed=0):
     B = _dev(wl.to_bf16_bits(g.standard_normal((K, N)).astype(np.float32)))
     table = {}
 
-    def gather_k(frac):
-        live = g.random((K, M // 128)) < frac
-        At = np.repeat(live, 128, axis=1).astype(np.float32) * g.standard_normal((K, M)).astype(np.float32)
+    def gather_k(frac, mt=128):
+        live = g.random((K, M // mt)) < frac
+        At = np.repeat(live, mt, axis=1).astype(np.float32) * g.standard_normal((K, M)).astype(np.float32)
         tA = _dev(wl.to_bf16_bits(At))
-        ix = pit.pit_build_index(tA, 1, 128, 0)
+        ix = pit.pit_build_index(tA, 1, mt, 0)
         C = torch.empty((M, N), dtype=torch.float32, device="cuda")
-        t = _time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, B, ix, 128, M, N, K, out=C))
+        t = _time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, B, ix, mt, M, N, K, out=C))
         return t / max(int(live.sum()), 1)
 
     def gather_m(slab, frac):
@@ -65,13 +73,51 @@ def measure(M=2048, K=4096, N=2048, keep=0.5, seed=0):
         t = _time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, tA, B, ix, slab, M, N, K, out=C))
         return t / max(int(live.sum()), 1)
 
-    for name, fn in [("gather_k", gather_k)] + [(f"gather_m_{s}", (lambda fr, s=s: gather_m(s, fr))) for s in (32, 64, 128, K)]:
-        key = name if not name.endswith(str(K)) else "gather_m_row"
+    for name, fn in [("gather_k", gather_k), ("gather_k_64", lambda fr: gather_k(fr, 64)), ("gather_k_32", lambda fr: gather_k(fr, 32))] + \
+                    [(f"gather_m_{s}", (lambda fr, s=s: gather_m(s, fr))) for s in (32, 64, 128, K)]:
+        key = name if not name.endswith("_" + str(K)) else "gather_m_row"
         table[key] = {"sparse_ns_per_tile": fn(keep) * 1e9, "dense_ns_per_tile": fn(1.0) * 1e9}
-    shapes = {"gather_k": [128, 1], "gather_m_32": [1, 32], "gather_m_64": [1, 64], "gather_m_128": [1, 128],
-              "gather_m_row": [1, K]}
+    for k, v in step_costs().items():
+        table.setdefault(k, {}).update(v)
+    shapes = {"gather_k": [128, 1], "gather_k_64": [64, 1], "gather_k_32": [32, 1], "dense_k": [128, 1],
+              "gather_m_32": [1, 32], "gather_m_64": [1, 64], "gather_m_128": [1, 128], "gather_m_row": [1, K]}
     return {"device": torch.cuda.get_device_name(0), "M": M, "K": K, "N": N, "keep": keep,
             "candidates": {k: {"micro_tile": shapes[k], **v} for k, v in table.items()}}
+
+
+def step_costs(n=4096, seed=1):
+    """Affine fit of a whole step (index build + product) over the number of covered micro-tiles, per tile height
+    of the GATHER_K kernel, and the dense kernel's time per micro-tile of the grid, on an n^3 product."""
+    g = np.random.default_rng(seed)
+    B = _dev(wl.to_bf16_bits(g.standard_normal((n, n)).astype(np.float32)))
+    vals = g.standard_normal((n, n)).astype(np.float32)
+    C = torch.empty((n, n), dtype=torch.float32, device="cuda")
+    out = {}
+    for name, mt in (("gather_k", 128), ("gather_k_64", 64), ("gather_k_32", 32)):
+        pts = []
+        for frac in (0.1, 0.6):
+            live = g.random((n, n // mt)) < frac
+            tA = _dev(wl.to_bf16_bits(np.repeat(live, mt, axis=1) * vals))
+            ix = pit.PitIndex.empty(n // mt, (n // mt) * n)
+            ws = torch.empty(pit.pit_build_index_workspace(n, n, 1, mt, 0), dtype=torch.uint8, device="cuda")
+
+            def step():
+                pit.pit_build_index(tA, 1, mt, 0, out=ix, ws=ws)
+                pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, tA, B, ix, mt, n, n, n, out=C)
+
+            pts.append((int(live.sum()), _time(step) * 1e9))
+        slope = (pts[1][1] - pts[0][1]) / (pts[1][0] - pts[0][0])
+        out[name] = {"step_ns_per_tile": slope, "step_fixed_ns": max(pts[0][1] - slope * pts[0][0], 0.0)}
+    # the dense kernel: the same fit over the micro-tiles of the whole grid, from two extents of k
+    tA = _dev(wl.to_bf16_bits(vals))
+    pts = []
+    for k in (n // 2, n):
+        t = _time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_DENSE_K, tA[:k], B[:k], None, 128, n, n, k, out=C)) * 1e9
+        pts.append((k * (n // 128), t))
+    slope = (pts[1][1] - pts[0][1]) / (pts[1][0] - pts[0][0])
+    out["dense_k"] = {"step_ns_per_tile": slope, "step_fixed_ns": max(pts[0][1] - slope * pts[0][0], 0.0),
+                      "dense_ns_per_tile": pts[1][1] / pts[1][0]}
+    return out
 
 
 def main():

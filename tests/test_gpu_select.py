@@ -86,3 +86,73 @@ def test_cover_count_at_table3_size(pit):
         assert got == orc.cover_count(D, mt, 1)
         ntiles = (4096 // mt) * 4096
         assert got == pytest.approx(ntiles * (1 - 0.95 ** (mt / 2)), rel=0.01)
+
+
+# ------------------------------------------------------------------ the dense kernel and Algorithm 1 end to end
+@pytest.mark.parametrize("mt", [128, 64, 32])
+def test_dense_kernel_is_the_product_with_no_index(pit, mt):
+    """PIT_GEMM_DENSE_K: identity addressing, every k multiplied; exact on integers, zeros in A or not."""
+    for prob in (None, 0.3):
+        w = wl.relu_ffn(M=384, K=333, N=256, seed=mt, integer=True, channel_live_prob=prob)
+        Xt, W = to_dev(w.Xt), to_dev(w.W)
+        C = torch.full((w.M, w.N), 5.0, device="cuda")
+        pit.pit_sread_gemm(pit.PIT_GEMM_DENSE_K, Xt, W, None, mt, w.M, w.N, w.K, out=C)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(w.Xt, w.W))
+    with pytest.raises(pit.PitError) as e:
+        pit.pit_sread_gemm(pit.PIT_GEMM_DENSE_K, Xt, W, None, 48, w.M, w.N, w.K)
+    assert e.value.code == pit.PIT_ESHAPE
+
+
+def _gather_k_candidates(costs):
+    """The (dense tile, PIT-axis) pairs the GATHER_K family offers on a K-major operand [K, M]: micro-tiles of
+    128, 64 and 32 consecutive m of one k, and the dense kernel."""
+    return [{"mt_rows": 1, "mt_cols": 128, "tile_cost": costs[0]}, {"mt_rows": 1, "mt_cols": 64, "tile_cost": costs[1]},
+            {"mt_rows": 1, "mt_cols": 32, "tile_cost": costs[2]}, {"mt_rows": 1, "mt_cols": 128, "tile_cost": costs[3], "dense": True}]
+
+
+@pytest.mark.parametrize("costs,want", [((1.0, 9.0, 9.0, 9.0), 0), ((9.0, 1.0, 9.0, 9.0), 1), ((9.0, 9.0, 1.0, 9.0), 2),
+                                        ((9.0, 9.0, 9.0, 0.01), 3)])
+def test_select_and_run_launches_the_winner(pit, costs, want):
+    """Whatever Algorithm 1 selects, the product must be the oracle's; the selection itself must be the oracle's
+    selection from the same samples, with CoverAlgo's counts taken on the GPU."""
+    w = wl.relu_ffn(M=512, K=420, N=256, seed=17, integer=True, channel_live_prob=0.3, live_block=32)
+    samples = [wl.relu_ffn(M=512, K=420, N=8, seed=18 + i, integer=True, channel_live_prob=0.3, live_block=32).Xt for i in range(2)]
+    cands = _gather_k_candidates(costs)
+    num = [[int(pit.pit_cover_count(to_dev(D), c["mt_rows"], c["mt_cols"]).item()) for c in cands] for D in samples]
+    grid = [[D.shape[0] * (D.shape[1] // c["mt_cols"]) for c in cands] for D in samples]
+    C = torch.full((w.M, w.N), -3.0, device="cuda")
+    _, chosen = pit.pit_select_and_run_gemm(cands, num, grid, to_dev(w.Xt), to_dev(w.W), w.M, w.N, w.K, out=C)
+    torch.cuda.synchronize()
+    assert chosen == want == orc.select_kernel([orc.to_f64(D) for D in samples], cands)[0]
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), orc.gemm_at(w.Xt, w.W))
+
+
+def test_select_and_run_with_the_profiled_costs(pit):
+    """With the committed profile of this GPU type, on the product the profile was taken on (4096^3): iid ReLU
+    zeros (98 % of the 32 x 1 micro-tiles live) fall back to the dense kernel and zeros correlated across tokens
+    pick a sparse kernel (paper Section 3.2).  The product of whichever kernel ran is checked on sampled rows."""
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(pit.__file__))
+    prof = json.load(open(os.path.join(here, "tile_cost_mi355x.json")))["candidates"]
+    names = ["gather_k", "gather_k_64", "gather_k_32", "dense_k"]
+    cands = _gather_k_candidates([prof[k]["step_ns_per_tile"] for k in names])
+    for c, k in zip(cands, names):
+        c["fixed_cost"] = prof[k]["step_fixed_ns"]
+    n = 4096
+    picks = {}
+    rows = np.random.default_rng(3).choice(n, 64, replace=False)
+    for name, prob in (("iid", None), ("correlated", 0.1)):
+        w = wl.relu_ffn(M=n, K=n, N=n, seed=1, channel_live_prob=prob)
+        Xt = to_dev(w.Xt)
+        num = [[int(pit.pit_cover_count(Xt, 1, c["mt_cols"]).item()) for c in cands]]
+        grid = [[w.K * (w.M // c["mt_cols"]) for c in cands]]
+        C, chosen = pit.pit_select_and_run_gemm(cands, num, grid, Xt, to_dev(w.W), w.M, w.N, w.K)
+        torch.cuda.synchronize()
+        picks[name] = chosen
+        assert num[0][:3] == [orc.cover_count(w.Xt, 1, mt) for mt in (128, 64, 32)]
+        ref = orc.gemm_at(np.ascontiguousarray(w.Xt[:, rows]), w.W)          # rows of C = columns of the K-major operand
+        mx, fro = orc.rel_errors(C[to_dev(rows)].cpu().numpy(), ref)
+        assert mx <= 2e-2 and fro <= 1e-3
+    assert picks["iid"] == 3 and picks["correlated"] in (0, 1, 2)

@@ -25,7 +25,7 @@ def _literal_selection(samples, candidates):
                             if float(D[i + a, j + b]) != 0.0:
                                 hit = True
                     n += 1 if hit else 0
-            cost += n * c["tile_cost"]
+            cost += c.get("fixed_cost", 0.0) + n * c["tile_cost"]
         if cost < best_cost:
             best, best_cost = ci, cost
     return best
@@ -104,3 +104,23 @@ def test_selection_moves_to_dense_as_sparsity_drops():
         picks.append(orc.select_kernel([D], cands)[0])
     assert picks[0] == 0 and picks[-1] == 2
     assert picks == sorted(picks)
+
+
+def test_fixed_cost_is_added_once_per_sample():
+    """The constant part of a run (the library's addition to the paper's proportional model): hand-computed costs
+    on a tensor whose covers are known, and a case where the constant alone moves the choice."""
+    D = np.zeros((8, 8), dtype=np.float32)
+    D[0, 0] = D[5, 6] = 1.0                          # two non-zeros: 2 tiles of 1 x 2, 2 of 4 x 4, grid of 4 x 4 = 4
+    cands = [{"mt_rows": 1, "mt_cols": 2, "tile_cost": 1.0, "fixed_cost": 10.0},
+             {"mt_rows": 4, "mt_cols": 4, "tile_cost": 3.0, "fixed_cost": 2.5},
+             {"mt_rows": 4, "mt_cols": 4, "tile_cost": 2.0, "dense": True}]
+    best, costs = orc.select_kernel([D, D, D], cands)
+    assert costs == [3 * (10.0 + 2 * 1.0), 3 * (2.5 + 2 * 3.0), 3 * (4 * 2.0)]
+    assert best == 2 == _literal_selection([D, D, D], cands)
+    cands[0]["fixed_cost"] = 0.0                     # the paper's formula: the fine micro-tile wins
+    assert orc.select_kernel([D], cands)[0] == 0 == _literal_selection([D], cands)
+    g = np.random.default_rng(11)
+    for _ in range(30):
+        samples = [(g.random((8, 8)) < 0.2).astype(np.float32) for _ in range(2)]
+        cc = [dict(c, fixed_cost=float(g.choice([0.0, 1.0, 4.0]))) for c in CANDS]
+        assert orc.select_kernel(samples, cc)[0] == _literal_selection(samples, cc)
