@@ -83,14 +83,48 @@ def sweep_point(pit, At, B, n, reps, cands, t_dense_lib):
     return rec
 
 
+def probe():
+    """Register-resident issue rate of the two MFMA shapes the kernels use (1 and 4 waves per SIMD), an empty
+    kernel's launch, and three dependent launches back to back (the floor of a three-kernel step)."""
+    import ctypes
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2301_10936_amd")
+    lib = ctypes.CDLL(os.path.join(here, "libpit_probe.so"))
+    lib.pit_probe_mfma.restype = ctypes.c_double
+    lib.pit_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    lib.pit_probe_empty.argtypes = [ctypes.c_void_p]
+    out = torch.zeros(4, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    res = {"compute_units": cus, "mfma": [], "launch": {}}
+    for shape, name in ((0, "v_mfma_f32_16x16x32_bf16"), (1, "v_mfma_f32_32x32x16_bf16")):
+        for waves_per_simd in (1, 4):
+            blocks, iters = cus * waves_per_simd, 20000
+            flops = [0.0]
+
+            def run():
+                flops[0] = lib.pit_probe_mfma(shape, blocks, iters, out.data_ptr(), st)
+
+            t = _time(run, 5)
+            per = t / (iters * 8.0) * 1e9
+            res["mfma"].append({"instruction": name, "waves_per_simd": waves_per_simd, "TFLOP_per_s": round(flops[0] / t / 1e12, 1),
+                                "ns_per_mfma_per_wave": round(per, 2)})
+    res["launch"]["empty_kernel_us"] = round(_time(lambda: lib.pit_probe_empty(st), 200) * 1e6, 2)
+    res["launch"]["three_dependent_empty_kernels_us"] = round(_time(lambda: [lib.pit_probe_empty(st) for _ in range(3)], 100) * 1e6, 2)
+    print(json.dumps(res, indent=1))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--table", action="store_true")
+    ap.add_argument("--probe", action="store_true", help="MFMA issue rates and launch floor instead of the sweeps")
     a = ap.parse_args()
     if not torch.cuda.is_available():
         print("bench_micro.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.probe:
+        probe()
+        return
     from paper_2301_10936_amd import pit, workloads as wl
     n = 4096
     g = np.random.default_rng(0)

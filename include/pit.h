@@ -113,6 +113,18 @@ int pit_build_index_static(const void* d_src, int dt, int rows, int cols, int64_
                            int mt_rows, int mt_cols, int pit_dim,
                            const pit_index* out, pit_stream stream);
 
+/*
+ * Debug aid.  The product kernels trust the index they are given: an entry outside the operand
+ * makes them read or write out of bounds (checking every entry inside the k loop would cost a
+ * compare and a branch per gathered row on the hot path; an index built by this library is in
+ * range by construction).  A caller that builds or edits an index itself can validate it first:
+ * *d_bad (device, int32) receives the number of violations -- entries outside [0, npit), entries
+ * not strictly above their predecessor within a segment, and segment bounds that are not
+ * 0 = seg_ptr[0] <= seg_ptr[s] <= seg_ptr[s + 1] <= cap.  npit = number of micro-tile coordinates
+ * along the PIT-axis.  Enqueued on `stream`; the caller reads *d_bad back when it wants to know.
+ */
+int pit_check_index(const pit_index* ix, int npit, int32_t* d_bad, pit_stream stream);
+
 /* Bytes of device workspace pit_build_route_index needs. */
 size_t pit_build_route_index_workspace(int T, int E);
 
@@ -245,7 +257,9 @@ typedef enum pit_gemm_mode {
  *   ix     index built by pit_build_index on A (or on a row mask) with the micro-tile named above.
  * Shape rules (else PIT_ESHAPE): N % 128 == 0; GATHER_M: mt % 32 == 0 and K % mt == 0;
  * GATHER_K and DENSE_K: mt in {32, 64, 128}, M % mt == 0.  Pointers 16-byte aligned, leading dimensions % 8 == 0.
- * Index entries outside the valid coordinate range are a caller error (not checked on the device).
+ * Index entries outside the valid coordinate range are a caller error (not checked by this call:
+ * see pit_check_index).  Grid limits (else PIT_ESHAPE): the worst-case number of row tiles of
+ * GATHER_M, M / 128 + nseg, must not exceed 65535.
  */
 int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void* d_B, int64_t ldb,
                    void* d_C, int64_t ldc, int M, int N, int K, int in_dt, int c_dt,

@@ -17,9 +17,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wno
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = False) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
-    cmd = ["hipcc", *FLAGS, "-o", LIB, *srcs]
+PROBE_LIB = os.path.join(HERE, "libpit_probe.so")     # measurement probes (bench_micro.py --probe), not the product
+
+
+def _compile(srcs, lib, verbose):
+    cmd = ["hipcc", *FLAGS, "-o", lib, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -29,6 +31,12 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = False) -> str:
+    srcs = [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    _compile(srcs, LIB, verbose)
+    _compile([os.path.join(CSRC, "pit_probe.hip")], PROBE_LIB, verbose)
     return LIB
 
 

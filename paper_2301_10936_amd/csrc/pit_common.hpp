@@ -36,4 +36,10 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 constexpr int kWave = 64;
 
+// pit_build_route_index that also clears, in `zero_rows` (row pitch zero_ld_bytes, zero_row_bytes per row, both
+// multiples of 16), the rows of the tokens whose expert id is out of range (zero_rows == nullptr: nothing cleared).
+int launch_route_index(const int32_t* d_expert_id, int T, int E, const pit_index* out, int32_t* d_status,
+                       void* d_ws, size_t ws_bytes, void* zero_rows, int64_t zero_ld_bytes, int zero_row_bytes,
+                       pit_stream stream);
+
 }  // namespace pit

@@ -403,12 +403,25 @@ k_relu_transpose_bitmap(const void* __restrict__ H, int64_t ldh_bytes, int token
 // ----------------------------------------------------------------------------------------------
 // pass 1 for routing decisions: segment e, bit t  <=>  expert_id[t] == e
 // ----------------------------------------------------------------------------------------------
+// A token whose id is outside [0, E) is listed nowhere; if zero_rows is given, its row of that matrix (the
+// output of the layer that the index is built for) is cleared here, by the whole wave, so that the caller
+// need not clear the matrix for the sake of tokens that normally do not exist.
 __global__ void __launch_bounds__(256)
-k_bitmap_route(const int32_t* __restrict__ expert_id, int T, int E, int W, u64* __restrict__ words) {
+k_bitmap_route(const int32_t* __restrict__ expert_id, int T, int E, int W, u64* __restrict__ words,
+               char* __restrict__ zero_rows, int64_t zero_ld_bytes, int zero_row_bytes) {
   const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (w >= W) return;
   const int t = w * 64 + lane_id();
   const int e = t < T ? expert_id[t] : -1;
+  if (zero_rows != nullptr) {
+    u64 bad = __ballot(t < T && (e < 0 || e >= E));
+    while (bad) {
+      const int l = __builtin_ctzll(bad);
+      bad &= bad - 1;
+      char* row = zero_rows + (int64_t)(w * 64 + l) * zero_ld_bytes;
+      for (int b = lane_id() * 16; b < zero_row_bytes; b += 64 * 16) *reinterpret_cast<uint4*>(row + b) = make_uint4(0, 0, 0, 0);
+    }
+  }
   for (int e0 = 0; e0 < E; e0 += 64) {
     u64 mine = 0;
     const int n = min(64, E - e0);
@@ -1042,7 +1055,14 @@ extern "C" size_t pit_build_route_index_workspace(int T, int E) {
 
 extern "C" int pit_build_route_index(const int32_t* d_expert_id, int T, int E, const pit_index* out,
                                      int32_t* d_status, void* d_ws, size_t ws_bytes, pit_stream stream) {
+  return pit::launch_route_index(d_expert_id, T, E, out, d_status, d_ws, ws_bytes, nullptr, 0, 0, stream);
+}
+
+int pit::launch_route_index(const int32_t* d_expert_id, int T, int E, const pit_index* out, int32_t* d_status,
+                            void* d_ws, size_t ws_bytes, void* zero_rows, int64_t zero_ld_bytes, int zero_row_bytes,
+                            pit_stream stream) {
   if (!out || !out->seg_ptr) return PIT_EINVAL;
+  if (zero_rows && (zero_row_bytes % 16 || zero_ld_bytes % 16 || !aligned(zero_rows, 16))) return PIT_EINVAL;
   if (T < 0 || E <= 0) return PIT_ESHAPE;
   if (out->nseg != E || out->cap < T) return PIT_ECAPACITY;
   if (out->bits) return PIT_EINVAL;
@@ -1054,9 +1074,51 @@ extern "C" int pit_build_route_index(const int32_t* d_expert_id, int T, int E, c
   char* ws = reinterpret_cast<char*>(d_ws);
   u64* words = reinterpret_cast<u64*>(ws);
   int32_t* cnt = reinterpret_cast<int32_t*>(ws + L.words_bytes);
-  hipLaunchKernelGGL(k_bitmap_route, dim3((L.W + 3) / 4), dim3(256), 0, st, d_expert_id, T, E, L.W, words);
+  hipLaunchKernelGGL(k_bitmap_route, dim3((L.W + 3) / 4), dim3(256), 0, st, d_expert_id, T, E, L.W, words,
+                     reinterpret_cast<char*>(zero_rows), zero_ld_bytes, zero_row_bytes);
   PIT_LAUNCH_CHECK();
   return launch_emit(L, words, cnt, nullptr, out, T, d_status, st);
+}
+
+// ----------------------------------------------------------------------------------------------
+// Debug aid: validate an index before handing it to a product kernel (the kernels themselves trust it).
+// ----------------------------------------------------------------------------------------------
+namespace pit {
+namespace {
+// one workgroup per segment; counts entries outside [0, npit), entries not strictly above their predecessor in
+// the segment, and segment bounds that are not 0 <= seg_ptr[s] <= seg_ptr[s + 1] <= cap (seg_ptr[0] must be 0)
+__global__ void __launch_bounds__(256)
+k_check_index(const int32_t* __restrict__ seg_ptr, const int32_t* __restrict__ idx, int nseg, int cap, int npit,
+              int32_t* __restrict__ bad) {
+  __shared__ int red[4];
+  const int s = blockIdx.x;
+  const int b = seg_ptr[s], e = seg_ptr[s + 1];
+  int n = 0;
+  const bool bounds_ok = b >= 0 && e >= b && e <= cap && (s != 0 || b == 0);
+  if (!bounds_ok) {
+    n = threadIdx.x == 0 ? 1 : 0;
+  } else {
+    for (int j = b + (int)threadIdx.x; j < e; j += 256) {
+      const int v = idx[j];
+      if (v < 0 || v >= npit || (j > b && idx[j - 1] >= v)) ++n;
+    }
+  }
+  const int total = block_sum_256(n, red);
+  if (threadIdx.x == 0 && total != 0) atomicAdd(bad, total);
+}
+}  // namespace
+}  // namespace pit
+
+extern "C" int pit_check_index(const pit_index* ix, int npit, int32_t* d_bad, pit_stream stream) {
+  if (!ix || !ix->seg_ptr || !d_bad || ix->nseg < 0 || ix->cap < 0 || npit < 0) return PIT_EINVAL;
+  if (ix->nseg > 0 && ix->cap > 0 && !ix->idx) return PIT_EINVAL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, d_bad, 1, 0);
+  PIT_LAUNCH_CHECK();
+  if (ix->nseg == 0) return PIT_OK;
+  hipLaunchKernelGGL(k_check_index, dim3((unsigned)ix->nseg), dim3(256), 0, st, ix->seg_ptr, ix->idx, ix->nseg, ix->cap, npit, d_bad);
+  PIT_LAUNCH_CHECK();
+  return PIT_OK;
 }
 
 // ----------------------------------------------------------------------------------------------

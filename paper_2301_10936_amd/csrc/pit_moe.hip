@@ -56,13 +56,11 @@ extern "C" int pit_moe_dispatch_gemm(const void* d_X, const int32_t* d_expert_id
   if (!d_X || !d_expert_id || !d_W1 || !d_W2 || !d_Y) return PIT_EINVAL;
   if (!aligned(d_X, 16) || !aligned(d_W1, 16) || !aligned(d_W2, 16) || !aligned(d_Y, 16)) return PIT_EINVAL;
 
-  int rc = pit_build_route_index(d_expert_id, T, E, &ix, d_status, ws + L.route_off, L.total - L.route_off, stream);
-  if (rc != PIT_OK) return rc;
-
+  // tokens with an invalid expert id are listed nowhere; their rows of Y are cleared by the index build itself
+  // (every other row is written by the second matmul's SWrite)
   const int y_esize = y_dt == PIT_F32 ? 4 : 2;
-  // tokens with an invalid expert id are listed nowhere; give their rows a defined value.  The
-  // fill is needed only then, but whether it is cannot be known on the host, so Y is cleared.
-  rc = launch_zero_rows(d_Y, (int64_t)d_model * y_esize, T, (int64_t)d_model * y_esize, st);
+  int rc = launch_route_index(d_expert_id, T, E, &ix, d_status, ws + L.route_off, L.total - L.route_off,
+                              d_Y, (int64_t)d_model * y_esize, d_model * y_esize, stream);
   if (rc != PIT_OK) return rc;
 
   void* H = ws + L.h_off;

@@ -24,7 +24,7 @@ PIT_GEMM_GATHER_M, PIT_GEMM_GATHER_K, PIT_GEMM_DENSE_K = 0, 1, 2
 _STATUS = {0: "PIT_OK", -1: "PIT_EINVAL", -2: "PIT_ESHAPE", -3: "PIT_ECAPACITY", -4: "PIT_EHIP"}
 
 EXPORTS = ["pit_last_hip_error", "pit_version", "pit_build_index_workspace", "pit_build_index",
-           "pit_build_index_static_capacity", "pit_build_index_static",
+           "pit_build_index_static_capacity", "pit_build_index_static", "pit_check_index",
            "pit_build_route_index_workspace", "pit_build_route_index",
            "pit_relu_channel_major_index_workspace", "pit_relu_channel_major_index",
            "pit_cover_count_workspace", "pit_cover_count", "pit_select_kernel", "pit_sread_gemm",
@@ -49,6 +49,8 @@ _lib.pit_build_index_static_capacity.restype = c_sz
 _lib.pit_build_index_static_capacity.argtypes = []
 _lib.pit_build_index_static.restype = c_int
 _lib.pit_build_index_static.argtypes = [c_vp, c_int, c_int, c_int, c_i64, c_int, c_int, c_int, _P, c_vp]
+_lib.pit_check_index.restype = c_int
+_lib.pit_check_index.argtypes = [_P, c_int, c_vp, c_vp]
 _lib.pit_build_route_index_workspace.restype = c_sz
 _lib.pit_build_route_index_workspace.argtypes = [c_int, c_int]
 _lib.pit_build_route_index.restype = c_int
@@ -181,6 +183,15 @@ def pit_build_index_static(src: torch.Tensor, mt_rows: int, mt_cols: int, pit_di
     ci = out.c()
     _check(_lib.pit_build_index_static(src.data_ptr(), _dt(src), rows, cols, src.stride(0) if rows > 1 else max(cols, src.stride(0)),
                                        mt_rows, mt_cols, pit_dim, ctypes.byref(ci), _stream()), "pit_build_index_static")
+    return out
+
+
+def pit_check_index(ix: PitIndex, npit: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Number of violations in an index (device int32[1]): see include/pit.h."""
+    if out is None:
+        out = torch.empty(1, dtype=torch.int32, device=ix.seg_ptr.device)
+    ci = ix.c()
+    _check(_lib.pit_check_index(ctypes.byref(ci), npit, out.data_ptr(), _stream()), "pit_check_index")
     return out
 
 

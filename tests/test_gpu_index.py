@@ -259,3 +259,26 @@ def test_error_returns(pit):
     with_bits = pit.PitIndex.empty(1, 64, want_bits=True)
     assert call(mt_c=64, idx=with_bits) == pit.PIT_EINVAL                  # bits need <= 32 elements
     torch.cuda.synchronize()
+
+
+def test_check_index_counts_violations(pit):
+    """pit_check_index: zero on what the library builds, and every planted fault of a hand-made index counted."""
+    w = wl.relu_ffn(M=256, K=300, N=8, seed=2, channel_live_prob=0.3)
+    ix = pit.pit_build_index(to_dev(w.Xt), 1, 128, 0)
+    assert int(pit.pit_check_index(ix, 300).item()) == 0
+    assert int(pit.pit_check_index(ix, 10).item()) > 0                      # the same lists against a shorter axis
+    sp = torch.tensor([0, 3, 3, 6], dtype=torch.int32, device="cuda")
+    idx = torch.tensor([1, 5, 9, 0, 2, 4, 0, 0], dtype=torch.int32, device="cuda")
+    good = pit.PitIndex(sp, idx, None, 3, 8)
+    assert int(pit.pit_check_index(good, 10).item()) == 0
+    idx2 = idx.clone(); idx2[2] = 10                                        # out of range (last of its segment)
+    assert int(pit.pit_check_index(pit.PitIndex(sp, idx2, None, 3, 8), 10).item()) == 1
+    idx3 = idx.clone(); idx3[4] = 0                                         # not above its predecessor (0 after 0)
+    assert int(pit.pit_check_index(pit.PitIndex(sp, idx3, None, 3, 8), 10).item()) == 1
+    idx4 = idx.clone(); idx4[0] = -1; idx4[5] = 2                           # negative; equal to its predecessor
+    assert int(pit.pit_check_index(pit.PitIndex(sp, idx4, None, 3, 8), 10).item()) == 2
+    sp2 = torch.tensor([0, 4, 3, 6], dtype=torch.int32, device="cuda")      # segment 1 ends before it starts
+    assert int(pit.pit_check_index(pit.PitIndex(sp2, idx, None, 3, 8), 10).item()) >= 1
+    sp3 = torch.tensor([0, 3, 3, 9], dtype=torch.int32, device="cuda")      # beyond the capacity
+    assert int(pit.pit_check_index(pit.PitIndex(sp3, idx, None, 3, 8), 10).item()) == 1
+    torch.cuda.synchronize()
