@@ -31,6 +31,7 @@
 // the row the index names (or to compact rows), optionally GELU + rounding to the input type.
 #include "pit_gemm.hpp"
 #include "pit_gemm_dev.hpp"
+#include <type_traits>
 
 namespace pit {
 namespace {
@@ -65,7 +66,7 @@ template <int WM, int WN, int NST, int GN> struct MTile {
   static_assert(GN == 2 || GN == 4, "wave arrangement");
   static_assert(TMW % 64 == 0, "rows of a tile");
   static_assert(TNW == 128 || TNW == 256, "the B swizzle assumes k-rows of 256 or 512 bytes");
-  static_assert(NST >= 2 && NST <= 6 && (NST - 1) * LOADS < 64, "stages in flight must fit the 6-bit counter");
+  static_assert(NST >= 2 && NST <= 8 && (NST - 1) * LOADS < 64, "stages in flight must fit the 6-bit counter");
 };
 
 template <bool BF, int EPI, int CT, int WM, int WN, int NST, int GN>
@@ -83,77 +84,70 @@ k_gather_m_lds(const GemmArgs g) {
   const int wm = wv / GN, wn = wv % GN;
 
   // ---------------------------------------------------------------- which tile is this workgroup?
-  // Consecutive workgroup ids go to different XCDs (8, each with its own L2).  Renumber so that XCD
-  // x works on row tiles x, x + 8, x + 16, .. and runs all column tiles of a row tile back to back:
-  // they read the same gathered A rows through the same L2.  (Row tiles stay interleaved over the
-  // XCDs because the grid is sized for the worst case and the surplus row tiles sit at its end.)
-  int tile_row, tile_col;
-  {
-    const int tn = gridDim.x, tm = gridDim.y;
-    const int lin = blockIdx.x + tn * blockIdx.y;
-    const int full = (tm >> 3) << 3;   // row tiles dealt out in rounds of 8
-    if (lin < full * tn) {
-      const int x = lin & 7, i = lin >> 3;
-      tile_row = (i / tn) * 8 + x;
-      tile_col = i % tn;
-    } else {
-      tile_row = lin / tn;
-      tile_col = lin - tile_row * tn;
-    }
-  }
+  // Consecutive workgroup ids go to different XCDs (8, each with its own L2).  The row tiles that exist (their
+  // number is known only here, from the segment lengths) are dealt out in 8 contiguous shares, one per XCD, and
+  // an XCD runs all column tiles of a row tile back to back: the column tiles read the same gathered A rows,
+  // and neighbouring row tiles of one segment (one expert) read the same B, through the same L2.  The grid is
+  // sized for the worst case; workgroups beyond an XCD's share leave at once.
+  const int tn = gridDim.x;
+  const int lin = blockIdx.x + tn * blockIdx.y;
+  const int xcd = lin & 7, slot = lin >> 3;
+  const int tile_col = slot % tn, row_in_share = slot / tn;
   const int n0 = tile_col * TNW;
-
-  int seg, list_len;
-  {
-    // linear row-tile number -> (segment, tile inside segment); every wave does the same search
-    const int tile = tile_row;
-    int acc = 0;
-    seg = -1;
-    int tile_in_seg = 0;
-    for (int s0 = 0; s0 < g.nseg; s0 += 64) {
-      const int s = s0 + lane;
-      int cnt = 0;
-      if (s < g.nseg) cnt = g.seg_ptr[s + 1] - g.seg_ptr[s];
-      const int nt = (cnt + TMW - 1) / TMW;
-      int inc = nt;
+  // One pass over the segment lengths gives the number of row tiles and, in the same registers, the segment and
+  // position of this workgroup's tile (up to 64 segments: one load per lane; more: a second pass).  Every load
+  // here is a round trip to memory on the critical path of the tile, so nothing is fetched twice.
+  int seg = -1, tile_in_seg = 0, seg_begin = 0, seg_cnt = 0, total_tiles = 0;
+  auto scan64 = [&](int s0, int& beg, int& cnt, int& nt) -> int {   // inclusive scan of the tile counts of 64 segments
+    const int s = s0 + lane;
+    beg = 0; cnt = 0;
+    if (s < g.nseg) { beg = g.seg_ptr[s]; cnt = g.seg_ptr[s + 1] - beg; }
+    nt = (cnt + TMW - 1) / TMW;
+    int inc = nt;
 #pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const int t = __shfl_up(inc, d);
-        if (lane >= d) inc += t;
-      }
+    for (int d = 1; d < 64; d <<= 1) {
+      const int t = __shfl_up(inc, d);
+      if (lane >= d) inc += t;
+    }
+    return inc;
+  };
+  auto locate = [&](int tile, int base, int inc, int nt, int beg, int cnt, int s0) {   // tile lies in this chunk
+    const unsigned long long hit = __ballot(base + inc > tile);
+    const int l = __builtin_ctzll(hit);
+    seg = s0 + l;
+    tile_in_seg = tile - (base + __shfl(inc, l) - __shfl(nt, l));
+    seg_begin = __shfl(beg, l);
+    seg_cnt = __shfl(cnt, l);
+  };
+  if (g.nseg <= 64) {
+    int beg, cnt, nt;
+    const int inc = scan64(0, beg, cnt, nt);
+    total_tiles = __shfl(inc, 63);
+    const int share = (total_tiles + 7) >> 3;
+    const int tile = xcd * share + row_in_share;
+    if (row_in_share >= share || tile >= total_tiles) return;
+    locate(tile, 0, inc, nt, beg, cnt, 0);
+  } else {
+    for (int s0 = 0; s0 < g.nseg; s0 += 64) {
+      int beg, cnt, nt;
+      total_tiles += __shfl(scan64(s0, beg, cnt, nt), 63);
+    }
+    const int share = (total_tiles + 7) >> 3;
+    const int tile = xcd * share + row_in_share;
+    if (row_in_share >= share || tile >= total_tiles) return;
+    int base = 0;
+    for (int s0 = 0; s0 < g.nseg; s0 += 64) {
+      int beg, cnt, nt;
+      const int inc = scan64(s0, beg, cnt, nt);
       const int total = __shfl(inc, 63);
-      if (tile < acc + total) {
-        const unsigned long long hit = __ballot(acc + inc > tile);
-        const int l = __builtin_ctzll(hit);
-        seg = s0 + l;
-        tile_in_seg = tile - (acc + __shfl(inc, l) - __shfl(nt, l));
-        break;
-      }
-      acc += total;
+      if (tile < base + total) { locate(tile, base, inc, nt, beg, cnt, s0); break; }
+      base += total;
     }
     if (seg < 0) return;
-    const int sb = g.seg_ptr[seg];
-    const int cnt = g.seg_ptr[seg + 1] - sb;
-    const int list_begin = sb + tile_in_seg * TMW;
-    list_len = min(TMW, cnt - tile_in_seg * TMW);
-    for (int r = tid; r < TMW; r += 256) {
-      // rows past the end of the list read the list's last row (a valid address); their results
-      // are never stored
-      const int v = g.idx[list_begin + min(r, list_len - 1)];
-      s_rows_a[r] = g.a_gather ? v : list_begin + min(r, list_len - 1);
-      s_rows_c[r] = r < list_len ? (g.c_scatter ? v : list_begin + r) : -1;
-    }
-    __syncthreads();
   }
   seg = __builtin_amdgcn_readfirstlane(seg);
-
-  f32x16_t acc[WM][WN];
-#pragma unroll
-  for (int i = 0; i < WM; ++i)
-#pragma unroll
-    for (int j = 0; j < WN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  const int list_begin = __builtin_amdgcn_readfirstlane(seg_begin + tile_in_seg * TMW);
+  const int list_len = __builtin_amdgcn_readfirstlane(min(TMW, seg_cnt - tile_in_seg * TMW));
 
   const int nsteps = g.slab / KS;                  // the k extent is a multiple of 32 (checked on the host)
 
@@ -161,15 +155,6 @@ k_gather_m_lds(const GemmArgs g) {
   const char* a_src = uniform_ptr(g.A);
   const char* b_src = uniform_ptr(reinterpret_cast<const char*>(g.B) + (int64_t)seg * g.b_seg_stride * 2);
   const uint32_t pitch_a = (uint32_t)(g.lda * 2), pitch_b = (uint32_t)(g.ldb * 2);
-  // A: load instruction j (this wave: j = wv + 4 jj) brings tile rows 16 j .. 16 j + 15; lane l -> row
-  // 16 j + l / 4, slot l % 4, which holds source chunk (l % 4) ^ ((row >> 2) & 3)
-  uint32_t a_off[LA];
-#pragma unroll
-  for (int jj = 0; jj < LA; ++jj) {
-    const int r = 16 * (wv + 4 * jj) + (lane >> 2);
-    const int c = (lane & 3) ^ ((r >> 2) & 3);
-    a_off[jj] = __umul24((uint32_t)s_rows_a[r], pitch_a) + (uint32_t)(c * 16);
-  }
   // B: a k-row of the tile is SPR slots of 16 B; load instruction j brings k-rows RPI j .. RPI j + RPI - 1;
   // lane l -> k-row RPI j + l / SPR, slot s = l % SPR, which holds source chunk ((s >> 2) ^ (k & 3)) * 4 + s % 4
   constexpr int SPR = TNW / 8, RPI = 64 / SPR;
@@ -182,14 +167,50 @@ k_gather_m_lds(const GemmArgs g) {
     b_off[jj] = __umul24((uint32_t)kk, pitch_b) + (uint32_t)((n0 + q * 32 + (s & 3) * 8) * 2);
   }
   const uint32_t b_step = 32u * pitch_b;           // bytes between two stages of B
-  auto issue = [&](int t, int u) {                    // stage t into buffer u = t % NST
-    const uint32_t buf = lds0 + (uint32_t)(u * T::STAGE);
-    const uint32_t ka = (uint32_t)t * 64u, kb = (uint32_t)t * b_step;
+  auto issue_b = [&](int t, int u) {                  // B rows of stage t into buffer u = t % NST
+    const uint32_t buf = lds0 + (uint32_t)(u * T::STAGE + T::A_STAGE), kb = (uint32_t)t * b_step;
+#pragma unroll
+    for (int jj = 0; jj < LB; ++jj) dma16(b_src, b_off[jj] + kb, buf + (uint32_t)((wv + 4 * jj) * 1024));
+  };
+  // The B rows of the first stages do not depend on the row numbers: they are requested now, and the row
+  // numbers (one more round trip: the index entries) are fetched while they travel.
+#pragma unroll
+  for (int t = 0; t < NST; ++t)
+    if (t < nsteps) issue_b(t, t);
+
+  for (int r = tid; r < TMW; r += 256) {
+    // rows past the end of the list read the list's last row (a valid address); their results
+    // are never stored
+    const int p = list_begin + min(r, list_len - 1);
+    const int v = (g.a_gather || g.c_scatter) ? g.idx[p] : 0;
+    s_rows_a[r] = g.a_gather ? v : p;
+    s_rows_c[r] = r < list_len ? (g.c_scatter ? v : list_begin + r) : -1;
+  }
+  __syncthreads();
+
+  f32x16_t acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // A: load instruction j (this wave: j = wv + 4 jj) brings tile rows 16 j .. 16 j + 15; lane l -> row
+  // 16 j + l / 4, slot l % 4, which holds source chunk (l % 4) ^ ((row >> 2) & 3)
+  uint32_t a_off[LA];
+#pragma unroll
+  for (int jj = 0; jj < LA; ++jj) {
+    const int r = 16 * (wv + 4 * jj) + (lane >> 2);
+    const int c = (lane & 3) ^ ((r >> 2) & 3);
+    a_off[jj] = __umul24((uint32_t)s_rows_a[r], pitch_a) + (uint32_t)(c * 16);
+  }
+  auto issue_a = [&](int t, int u) {
+    const uint32_t buf = lds0 + (uint32_t)(u * T::STAGE), ka = (uint32_t)t * 64u;
 #pragma unroll
     for (int jj = 0; jj < LA; ++jj) dma16(a_src, a_off[jj] + ka, buf + (uint32_t)((wv + 4 * jj) * 1024));
-#pragma unroll
-    for (int jj = 0; jj < LB; ++jj) dma16(b_src, b_off[jj] + kb, buf + (uint32_t)(T::A_STAGE + (wv + 4 * jj) * 1024));
   };
+  auto issue = [&](int t, int u) { issue_a(t, u); issue_b(t, u); };   // stage t into buffer u = t % NST
 
   // ---------------------------------------------------------------- operand reads: lane constants
   // A: row block i, k-substep ks -> row wm * 32 WM + 32 i + lane % 32, chunk 2 ks + lane / 32 (at slot chunk ^ xa,
@@ -210,23 +231,28 @@ k_gather_m_lds(const GemmArgs g) {
   const int live_i = __builtin_amdgcn_readfirstlane(max(0, min(WM, (list_len - wm * 32 * WM + 31) >> 5)));
 
   struct Frags { u32x4_t a[WM], b[WN]; };
-  auto read_frags = [&](int u, int ks, Frags& f) {     // u = buffer of the stage (compile-time after unrolling)
-    const uint32_t so = (uint32_t)(u * T::STAGE);
+  // FULL (compile time): every row block of the wave is live -- no conditions at all, so that a run of stages
+  // is one basic block and the compiler can place its LDS waits precisely and spread the reads among the MFMAs
+  // (with branches in between it falls back to a full wait in front of every read).
+  auto read_frags = [&](uint32_t so, int ks, Frags& f, auto full) {     // so = byte offset of the stage's buffer
+    constexpr bool FULL = decltype(full)::value;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
-      if (i < live_i) f.a[i] = lds_read_frag(a_rd[ks] + so + (uint32_t)(i * 2048));
-    if (live_i > 0)
+      if (FULL || i < live_i) f.a[i] = lds_read_frag(a_rd[ks] + so + (uint32_t)(i * 2048));
+    if (FULL || live_i > 0) {
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-      const uint32_t at = b_rd[j] + so + (uint32_t)(ks * 16 * (TNW * 2));
-      const uint2 lo = lds_tr(at), hi = lds_tr(at + 4 * (TNW * 2));
-      f.b[j] = u32x4_t{lo.x, lo.y, hi.x, hi.y};
+      for (int j = 0; j < WN; ++j) {
+        const uint32_t at = b_rd[j] + so + (uint32_t)(ks * 16 * (TNW * 2));
+        const uint2 lo = lds_tr(at), hi = lds_tr(at + 4 * (TNW * 2));
+        f.b[j] = u32x4_t{lo.x, lo.y, hi.x, hi.y};
+      }
     }
   };
-  auto mfmas = [&](const Frags& f) {
+  auto mfmas = [&](const Frags& f, auto full) {
+    constexpr bool FULL = decltype(full)::value;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
-      if (i < live_i) {
+      if (FULL || i < live_i) {
 #pragma unroll
         for (int j = 0; j < WN; ++j)
           // operands swapped: the accumulator holds the 32 x 32 block transposed (lane = row of C,
@@ -237,7 +263,9 @@ k_gather_m_lds(const GemmArgs g) {
 
   // wait until this wave's loads of a stage have landed while `younger` later stages stay in flight
   auto wait_stage = [&](int younger) {
-    if constexpr (NST >= 6) { if (younger >= 5) { PIT_WAIT_VMCNT(5 * T::LOADS); return; } }
+    if constexpr (NST >= 8) { if (younger >= 7) { PIT_WAIT_VMCNT(7 * T::LOADS); return; } }
+    if constexpr (NST >= 7) { if (younger == 6) { PIT_WAIT_VMCNT(6 * T::LOADS); return; } }
+    if constexpr (NST >= 6) { if (younger == 5) { PIT_WAIT_VMCNT(5 * T::LOADS); return; } }
     if constexpr (NST >= 5) { if (younger == 4) { PIT_WAIT_VMCNT(4 * T::LOADS); return; } }
     if constexpr (NST >= 4) { if (younger == 3) { PIT_WAIT_VMCNT(3 * T::LOADS); return; } }
     if constexpr (NST >= 3) { if (younger == 2) { PIT_WAIT_VMCNT(2 * T::LOADS); return; } }
@@ -250,30 +278,47 @@ k_gather_m_lds(const GemmArgs g) {
   // so buffer s % NST takes the loads of stage s + NST, and stage s + 1 has landed for everyone, so the
   // operands of its first half are requested before the MFMAs of the second half of stage s -- every LDS read
   // has a group of MFMAs to hide behind, and NST - 1 stages of loads are in flight.
-  if (nsteps > 0) {
+  // The steady state (stages whose stage s + NST exists) runs NST stages per trip without a branch; the last
+  // stages run through the general form.
+  auto pipeline = [&](auto full) {
+    // (the B rows of these stages are under way since before the row numbers were fetched; a full wait here:
+    // the A rows of the first NST stages were requested together and land together)
 #pragma unroll
     for (int t = 0; t < NST; ++t)
-      if (t < nsteps) issue(t, t);
-    wait_stage(min(NST - 1, nsteps - 1));
+      if (t < nsteps) issue_a(t, t);
+    PIT_WAIT_VMCNT(0);
     PIT_LDS_BARRIER();
     Frags f0, f1;
-    read_frags(0, 0, f0);
-    for (int s0 = 0; s0 < nsteps; s0 += NST) {
+    read_frags(0u, 0, f0, full);
+    int s0 = 0;
+    for (; s0 + 2 * NST - 1 < nsteps; s0 += NST) {
 #pragma unroll
       for (int u = 0; u < NST; ++u) {
-        const int s = s0 + u;
-        if (s >= nsteps) break;
-        read_frags(u, 1, f1);
-        mfmas(f0);
-        if (s + 1 < nsteps) {
-          wait_stage(min(NST - 2, nsteps - 2 - s));
-          PIT_LDS_BARRIER();
-          if (s + NST < nsteps) issue(s + NST, u);
-          read_frags((u + 1) % NST, 0, f0);
-        }
-        mfmas(f1);
+        read_frags((uint32_t)(u * T::STAGE), 1, f1, full);
+        mfmas(f0, full);
+        PIT_WAIT_VMCNT((NST - 2) * T::LOADS);
+        PIT_LDS_BARRIER();
+        issue(s0 + u + NST, u);
+        read_frags((uint32_t)(((u + 1) % NST) * T::STAGE), 0, f0, full);
+        mfmas(f1, full);
       }
     }
+    for (int s = s0; s < nsteps; ++s) {          // s0 is a multiple of NST: buffers continue at 0
+      const int u = s - s0 < NST ? s - s0 : s - s0 - NST;
+      read_frags((uint32_t)(u * T::STAGE), 1, f1, full);
+      mfmas(f0, full);
+      if (s + 1 < nsteps) {
+        wait_stage(min(NST - 2, nsteps - 2 - s));
+        PIT_LDS_BARRIER();
+        if (s + NST < nsteps) issue(s + NST, u);
+        read_frags((uint32_t)((u + 1 == NST ? 0 : u + 1) * T::STAGE), 0, f0, full);
+      }
+      mfmas(f1, full);
+    }
+  };
+  if (nsteps > 0) {
+    if (live_i == WM) pipeline(std::true_type{});
+    else pipeline(std::false_type{});
   }
 
   // ---------------------------------------------------------------- SWrite
@@ -312,8 +357,9 @@ template <bool BF, int EPI, int CT, int WM, int WN, int NST, int GN = 2>
 int launch_cfg(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
   using T = MTile<WM, WN, NST, GN>;
   const int64_t max_tiles = total_rows / T::TMW + g.nseg;      // sum over segments of ceil(count / TMW)
-  if (max_tiles > 65535) return PIT_ESHAPE;
-  dim3 grid((unsigned)(g.N / T::TNW), (unsigned)max_tiles);
+  if (max_tiles > 65528) return PIT_ESHAPE;
+  // (row tiles rounded up to a multiple of 8: every XCD then has room for its share of the tiles that exist)
+  dim3 grid((unsigned)(g.N / T::TNW), (unsigned)((max_tiles + 7) & ~(int64_t)7));
   hipLaunchKernelGGL((k_gather_m_lds<BF, EPI, CT, WM, WN, NST, GN>), grid, dim3(256), 0, st, g);
   PIT_LAUNCH_CHECK();
   return PIT_OK;
@@ -321,8 +367,9 @@ int launch_cfg(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
 
 // Tile shape by the shape of the product.  128 x 256 (a wave owns 64 x 128) where N allows: fewer bytes through
 // LDS per MFMA and fewer workgroups' worth of set-up than 128 x 128.  (Measured on the padded-batch product,
-// 8364 x 1024 x 4096: 128 x 128 with a ring of 4 stages 126-130 us, 256 x 128 115-121, 128 x 256 112-119; on the
-// mixture-of-experts call 209-211, 240-271 (rows of small experts are padded to 256) and 194-202 us.)
+// 8364 x 1024 x 4096: 128 x 128 with a ring of 3 or 4 stages 127 us, 256 x 128 117, 128 x 256 108-115; on the
+// mixture-of-experts call 189-193, 230 (rows of small experts are padded to 256) and 177 us.  Rings of 5 or 6 stages
+// with one workgroup per compute unit: no gain on either.)
 template <bool BF, int EPI, int CT>
 int launch_shape(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
   // (a product too small to give every compute unit a 128 x 256 tile even in the worst case takes 128 x 128)
