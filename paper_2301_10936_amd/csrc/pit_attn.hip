@@ -127,36 +127,46 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
   // wave, so the loop needs no workgroup barrier, and it is software-pipelined: the list entries of
   // chunk i + 2 and the K and V rows of chunk i + 1 are requested before chunk i is computed.
   const int my_chunks = nchunks > wv ? (nchunks - wv + 3) >> 2 : 0;
+  // Every load of the loop is unconditional (positions past the end of the list are clamped to its last entry
+  // and the value is then replaced by "no key"): a conditional load is a branch, and across a branch the
+  // compiler waits for ALL loads in flight, the next chunk's included, which would undo the pipelining below.
+  // (The loop only runs when the list is not empty.)
   auto load_key = [&](int i, int& key, uint32_t& bw) {
-    key = -1;
-    bw = 0u;
-    if (i < my_chunks) {
-      const int kk = (wv + 4 * i) * KC + ql;
-      if (kk < list_len) { key = idx[list_begin + kk]; bw = bits[list_begin + kk]; }
-    }
+    const int kk = (wv + 4 * i) * KC + ql;
+    const bool ok = i < my_chunks && kk < list_len;
+    const int pos = list_begin + min(kk, list_len - 1);
+    const int k = idx[pos];
+    const uint32_t b = bits[pos];
+    key = ok ? k : -1;
+    bw = ok ? b : 0u;
   };
   // SRead: the K and V rows of a chunk (32 x 128 B each) are fetched whole, 8 lanes x 16 B per row, so
-  // that every 128-byte line is requested once; both go through LDS on their way to the operands
+  // that every 128-byte line is requested once; both go through LDS on their way to the operands.  A
+  // position without a key reads row 0 and gets zeros instead (its probabilities are zero, but 0 x Inf is not).
   auto load_kv = [&](int key, uint4 (&kf)[4], uint4 (&vr)[4]) {
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int x = it * 64 + lane;
       const int krow = __shfl(key, x >> 3);
-      kf[it] = make_uint4(0, 0, 0, 0);
-      vr[it] = make_uint4(0, 0, 0, 0);
-      if (krow >= 0) {
-        kf[it] = *reinterpret_cast<const uint4*>(K + head_off + (int64_t)krow * HD + (x & 7) * 8);
-        vr[it] = *reinterpret_cast<const uint4*>(V + head_off + (int64_t)krow * HD + (x & 7) * 8);
-      }
+      const int64_t at = head_off + (int64_t)max(krow, 0) * HD + (x & 7) * 8;
+      const uint4 kq = *reinterpret_cast<const uint4*>(K + at);
+      const uint4 vq = *reinterpret_cast<const uint4*>(V + at);
+      const bool ok = krow >= 0;
+      kf[it] = make_uint4(ok ? kq.x : 0u, ok ? kq.y : 0u, ok ? kq.z : 0u, ok ? kq.w : 0u);
+      vr[it] = make_uint4(ok ? vq.x : 0u, ok ? vq.y : 0u, ok ? vq.z : 0u, ok ? vq.w : 0u);
     }
   };
 
   int key_a, key_b;
   uint32_t bw_a, bw_b;
   uint4 kf0[4], vr0[4], kf1[4], vr1[4];
-  load_key(0, key_a, bw_a);
-  load_key(1, key_b, bw_b);
-  load_kv(key_a, kf0, vr0);
+  key_a = key_b = -1;
+  bw_a = bw_b = 0u;
+  if (my_chunks > 0) {
+    load_key(0, key_a, bw_a);
+    load_key(1, key_b, bw_b);
+    load_kv(key_a, kf0, vr0);
+  }
   // one chunk: key_a / bw_a belong to chunk i (rows in kf, vr), key_b / bw_b to chunk i + 1
   auto step = [&](int i, uint4 (&kf)[4], uint4 (&vr)[4], uint4 (&kf_n)[4], uint4 (&vr_n)[4]) {
     int key_c;
@@ -164,7 +174,7 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
     load_key(i + 2, key_c, bw_c);
     load_kv(key_b, kf_n, vr_n);
 
-    if (h == 0) s_bits[wv][ql] = bw_a;
+    s_bits[wv][ql] = bw_a;               // (both halves of the wave hold the same word for query ql)
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int x = it * 64 + lane;
