@@ -1,9 +1,11 @@
 // pit_sparse_attn: dynamic sparse attention with the key axis as PIT-axis (paper Section 5.1,
 // Longformer; Table 1, BatchMatMul).  Micro-tile = 32 queries x 1 key.
 //
-//   1. pit_build_index on the [S x S] byte mask (32 x 1 micro-tiles, PIT-axis = keys) gives, for
-//      every block of 32 queries, the ascending list of keys at least one of them attends to, and
-//      per listed key a 32-bit word saying which of the 32 queries do.
+//   1. The index of the [S x S] byte mask (32 x 1 micro-tiles, PIT-axis = keys) gives, for every
+//      block of 32 queries, the ascending list of keys at least one of them attends to, and per
+//      listed key a 32-bit word saying which of the 32 queries do.  It is built in one launch
+//      (k_mask_index_q32: the lists sit at fixed places, one workgroup per query block), or by
+//      pit_build_index when the mask cannot be read 16 bytes at a time.
 //   2. One workgroup per (query block, head); its 4 wavefronts take the key list in chunks of 32
 //      keys, round-robin, each with its own running softmax state, merged at the end.  A wave's
 //      loop has no workgroup barrier and keeps the loads of its next chunk (and the list entries
@@ -81,7 +83,7 @@ template <bool BF, int OT>
 __global__ void __launch_bounds__(256)
 k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
               const int32_t* __restrict__ seg_ptr, const int32_t* __restrict__ idx, const uint32_t* __restrict__ bits,
-              void* __restrict__ O, int S, float scale_log2e) {
+              int list_stride, void* __restrict__ O, int S, float scale_log2e) {
   // per wave: its V tile and its K tile (8 KiB, private); after the loop the same 8 KiB carry the
   // wave's partial output to wave 0 (32 floats per lane, laid out [value][lane])
   __shared__ __attribute__((aligned(1024))) char s_kv[4][2 * V_TILE_BYTES];
@@ -102,8 +104,10 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
   }
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int h = lane >> 5, ql = lane & 31;
-  const int list_begin = seg_ptr[qb];
-  const int list_len = seg_ptr[qb + 1] - list_begin;
+  // list_stride > 0: the list of query block qb starts at qb * list_stride and seg_ptr[qb] is its length
+  // (k_mask_index_q32 below); else seg_ptr is the exclusive prefix pit_build_index writes
+  const int list_begin = list_stride > 0 ? qb * list_stride : seg_ptr[qb];
+  const int list_len = list_stride > 0 ? seg_ptr[qb] : seg_ptr[qb + 1] - list_begin;
   const int nchunks = (list_len + KC - 1) / KC;
   const int64_t head_off = (int64_t)head * S * HD;
 
@@ -330,6 +334,93 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
     }
 }
 
+// ----------------------------------------------------------------------------------------------
+// The index of the [S x S] byte mask at 32 x 1 (PIT-axis = keys) with occupancy words, in ONE launch
+// (paper Section 3.3: detection of the non-zero micro-tiles and their ordered list).  The attention
+// kernel is the only reader of this index, so the list of every query block may sit at a fixed place,
+// qb * S, with its length beside it; no prefix over the blocks is needed and one workgroup can do
+// detection, scan and ordered emit for its block without waiting for any other.
+// A thread owns 16 consecutive keys and loads them for the 32 queries of the block (16 B per row, a
+// wave reads 1 KiB of a mask row at a time); the non-zero test runs on four bytes at once and leaves,
+// per group of 8 queries, a byte of occupancy bits per key; four such bytes make the key's word.
+// Entries are written in ascending key order: threads, waves and passes of 4096 keys are in key order
+// and positions come from an exclusive scan of the per-thread counts.
+// ----------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_mask_index_q32(const uint8_t* __restrict__ mask, int S, int32_t* __restrict__ cnt,
+                 int32_t* __restrict__ idx, uint32_t* __restrict__ bits) {
+  __shared__ int s_wave[4];
+  const int qb = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const uint8_t* base = mask + (int64_t)qb * QB * S;
+  int32_t* out_i = idx + (int64_t)qb * S;
+  uint32_t* out_b = bits + (int64_t)qb * S;
+  int run = 0;                                    // entries written by earlier passes (uniform)
+  for (int c_base = 0; c_base < S; c_base += 4096) {
+    const int c0 = c_base + tid * 16;
+    uint32_t acc[4][4];                           // [group of 8 queries][4 keys]: byte j = the 8 queries' bits of key 4 w + j
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) acc[q][w] = 0;
+    if (c0 < S) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4*>(base + (int64_t)(8 * q + i) * S + c0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t d[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            // bit 7 of every non-zero byte, moved to bit i of that byte
+            const uint32_t nz = (((d[w] & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | d[w]) & 0x80808080u;
+            acc[q][w] |= nz >> (7 - i);
+          }
+        }
+      }
+    }
+    uint32_t o[16];
+    uint32_t flags = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int w = j >> 2;
+      const uint32_t b = (uint32_t)(j & 3);
+      // byte b of the four groups' words -> bytes 0..3 of the key's occupancy word (selector 0x0c = zero byte)
+      const uint32_t lo = __builtin_amdgcn_perm(acc[1][w], acc[0][w], 0x0c0c0000u | ((4u + b) << 8) | b);
+      const uint32_t hi = __builtin_amdgcn_perm(acc[3][w], acc[2][w], 0x00000c0cu | ((4u + b) << 24) | (b << 16));
+      o[j] = lo | hi;
+      flags |= (o[j] != 0 ? 1u : 0u) << j;
+    }
+    const int mine = __builtin_popcount(flags);
+    int inc = mine;
+#pragma unroll
+    for (int dd = 1; dd < 64; dd <<= 1) {
+      const int t = __shfl_up(inc, dd);
+      if (lane >= dd) inc += t;
+    }
+    if (lane == 63) s_wave[wv] = inc;
+    __syncthreads();
+    int pos = run + inc - mine, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int x = s_wave[w];
+      if (w < wv) pos += x;
+      total += x;
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if (o[j] != 0) {
+        out_i[pos] = c0 + j;
+        out_b[pos] = o[j];
+        ++pos;
+      }
+    run += total;
+    __syncthreads();                              // s_wave is rewritten by the next pass
+  }
+  if (tid == 0) cnt[qb] = run;
+}
+
 struct AttnWs {
   size_t seg_ptr_off, idx_off, bits_off, build_off, total;
   int nseg, cap;
@@ -378,17 +469,26 @@ extern "C" int pit_sparse_attn(const void* d_Q, const void* d_K, const void* d_V
   ix.bits = reinterpret_cast<uint32_t*>(ws + L.bits_off);
   ix.nseg = L.nseg;
   ix.cap = L.cap;
-  int rc = pit_build_index(d_mask, PIT_U8, S, S, S, QB, 1, 1, &ix, ws + L.build_off, L.total - L.build_off, stream);
-  if (rc != PIT_OK) return rc;
-
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  // one launch when the mask rows can be read 16 bytes at a time (S is a multiple of 32, so the base decides),
+  // else the general index build (bitmap pass + ordered emit) with the same lists behind an exclusive prefix
+  int list_stride = 0;
+  if (aligned(d_mask, 16) && (int64_t)L.nseg * S < (1ll << 31)) {
+    list_stride = S;
+    hipLaunchKernelGGL(k_mask_index_q32, dim3((unsigned)L.nseg), dim3(256), 0, st, d_mask, S, ix.seg_ptr, ix.idx, ix.bits);
+    PIT_LAUNCH_CHECK();
+  } else {
+    const int rc = pit_build_index(d_mask, PIT_U8, S, S, S, QB, 1, 1, &ix, ws + L.build_off, L.total - L.build_off, stream);
+    if (rc != PIT_OK) return rc;
+  }
+
   const float c = scale * 1.4426950408889634f;
   const uint16_t* q = reinterpret_cast<const uint16_t*>(d_Q);
   const uint16_t* k = reinterpret_cast<const uint16_t*>(d_K);
   const uint16_t* v = reinterpret_cast<const uint16_t*>(d_V);
   dim3 grid((unsigned)L.nseg, (unsigned)H);
 #define PIT_ATTN_LAUNCH(BF, OT) \
-  hipLaunchKernelGGL((k_sparse_attn<BF, OT>), grid, dim3(256), 0, st, q, k, v, ix.seg_ptr, ix.idx, ix.bits, d_O, S, c)
+  hipLaunchKernelGGL((k_sparse_attn<BF, OT>), grid, dim3(256), 0, st, q, k, v, ix.seg_ptr, ix.idx, ix.bits, list_stride, d_O, S, c)
   const int ot = o_dt == PIT_F32 ? 0 : (o_dt == PIT_BF16 ? 1 : 2);
   if (in_dt == PIT_BF16) {
     if (ot == 0) PIT_ATTN_LAUNCH(true, 0); else if (ot == 1) PIT_ATTN_LAUNCH(true, 1); else PIT_ATTN_LAUNCH(true, 2);

@@ -121,3 +121,28 @@ def test_values_far_outside_the_fp16_range(pit):
     O1 = _run(pit, w, mask=m).cpu().numpy()
     Vq = orc.to_f64(w.V)
     assert np.array_equal(O1[2], np.broadcast_to(Vq[2, 1], (256, 64))) and np.all(O1[2, 0] != 0)
+
+
+def test_key_lists_longer_than_one_pass_of_the_index_kernel(pit):
+    # S = 4256: the one-launch index of the mask walks the keys in passes of 4096, so the lists of a
+    # query block continue in a second pass whose last threads lie beyond the row
+    w = wl.sparse_attn(H=1, S=4256, window=64, density=0.02, seed=31)
+    O = _run(pit, w, sentinel=9.0)
+    assert_close(O, orc.sparse_attn(w.Q, w.K, w.V, w.mask, w.scale), "sparse_attn S=4256")
+
+
+def test_mask_at_an_odd_address_takes_the_general_index_build(pit):
+    # a mask whose rows cannot be read 16 bytes at a time goes through pit_build_index instead of the
+    # one-launch index; both must give the same attention
+    w = wl.sparse_attn(H=2, S=160, window=32, density=0.2, seed=32)
+    S = 160
+    buf = torch.zeros(S * S + 16, dtype=torch.uint8, device=dev())
+    odd = buf[3:3 + S * S].view(S, S)
+    odd.copy_(to_dev(w.mask))
+    assert odd.data_ptr() % 16 != 0
+    Q, K, V = to_dev(w.Q), to_dev(w.K), to_dev(w.V)
+    O_odd = pit.pit_sparse_attn(Q, K, V, odd, w.scale)
+    O_al = pit.pit_sparse_attn(Q, K, V, to_dev(w.mask), w.scale)
+    torch.cuda.synchronize()
+    assert_close(O_odd, orc.sparse_attn(w.Q, w.K, w.V, w.mask, w.scale), "sparse_attn, mask at an odd address")
+    assert torch.equal(O_odd, O_al)
