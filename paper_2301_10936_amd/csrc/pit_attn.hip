@@ -71,6 +71,27 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// Direct global -> LDS load of 16 bytes per lane: lane i's bytes land at lds_wave_base + 16 i (base and
+// lds_wave_base are wave-uniform).  Nothing passes through registers and no LDS write is issued by the wave.
+__device__ __forceinline__ void dma16(const char* base, uint32_t byte_off, uint32_t lds_wave_base) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(m0v), "v"(byte_off), "s"(reinterpret_cast<uint64_t>(base)) : "memory", "m0");
+}
+// The same for 4 bytes per lane (lane i's dword lands at lds_wave_base + 4 i); lanes that are switched off
+// neither load nor write.
+__device__ __forceinline__ void dma4(const void* base, uint32_t byte_off, uint32_t lds_wave_base) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :: "s"(m0v), "v"(byte_off), "s"(reinterpret_cast<uint64_t>(base)) : "memory", "m0");
+}
+// The compiler's own wait counts know nothing of these loads, so the chunk loop issues and awaits every one of
+// its loads by hand -- and all of them land in LDS, never in a register that the compiler might copy while
+// the load is still under way.  wait_loads: every vector-memory operation of this wave has completed.
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// wait for this wave's LDS operations (reads of a tile must have returned before a direct load refills it)
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 // byte offset of 16-byte chunk c16 (8 d) of key row r inside a V tile [32 keys][64 d]; the two
 // 64-byte halves of a row are swapped on rows with (r >> 1) odd so that the 4 consecutive rows a
 // transposing read touches land in 4 different quarters of the 256-byte bank row.
@@ -80,14 +101,15 @@ __device__ __forceinline__ uint32_t v_off(int r, int c16) {
 
 // OT: 0 = fp32, 1 = bf16, 2 = fp16 output
 template <bool BF, int OT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 3)
 k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
               const int32_t* __restrict__ seg_ptr, const int32_t* __restrict__ idx, const uint32_t* __restrict__ bits,
               int list_stride, void* __restrict__ O, int S, float scale_log2e) {
-  // per wave: its V tile and its K tile (8 KiB, private); after the loop the same 8 KiB carry the
+  // per wave (private): two V tiles and one K tile of 4 KiB; after the loop the first 8 KiB carry the
   // wave's partial output to wave 0 (32 floats per lane, laid out [value][lane])
-  __shared__ __attribute__((aligned(1024))) char s_kv[4][2 * V_TILE_BYTES];
-  __shared__ __attribute__((aligned(16))) uint32_t s_bits[4][KC];
+  __shared__ __attribute__((aligned(1024))) char s_kv[4][3 * V_TILE_BYTES];
+  // per wave, for two chunks: the 32 listed keys, then their 32 occupancy words
+  __shared__ __attribute__((aligned(256))) uint32_t s_list[4][2][2 * KC];
   __shared__ float s_ml[3][2][64];
 
   // Consecutive workgroup ids go to different XCDs (8, each with its own L2): renumber so that an XCD
@@ -124,92 +146,105 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
 
-  const uint32_t v_lds = (uint32_t)(uintptr_t)(PIT_LDS char*)s_kv[wv];
-  const uint32_t k_lds = v_lds + V_TILE_BYTES;
+  const uint32_t v_lds0 = (uint32_t)(uintptr_t)(PIT_LDS char*)s_kv[wv];
+  const uint32_t k_lds = v_lds0 + 2 * V_TILE_BYTES;
+  const char* k_head = reinterpret_cast<const char*>(K + head_off);
+  const char* v_head = reinterpret_cast<const char*>(V + head_off);
 
-  // This wave's chunks are wv, wv + 4, ...  The V tile and the mask words in LDS are private to the
-  // wave, so the loop needs no workgroup barrier, and it is software-pipelined: the list entries of
-  // chunk i + 2 and the K and V rows of chunk i + 1 are requested before chunk i is computed.
+  // This wave's chunks are wv, wv + 4, ...  The tiles and the mask words in LDS are private to the wave, so
+  // the loop needs no workgroup barrier, and it is software-pipelined: while chunk i is computed, the list
+  // entries of chunk i + 2 and the K and V rows of chunk i + 1 are under way.
   const int my_chunks = nchunks > wv ? (nchunks - wv + 3) >> 2 : 0;
-  // Every load of the loop is unconditional (positions past the end of the list are clamped to its last entry
-  // and the value is then replaced by "no key"): a conditional load is a branch, and across a branch the
-  // compiler waits for ALL loads in flight, the next chunk's included, which would undo the pipelining below.
-  // (The loop only runs when the list is not empty.)
-  auto load_key = [&](int i, int& key, uint32_t& bw) {
+  // SRead.  The K and V rows of a chunk (32 x 128 B each) travel global -> LDS directly, 8 lanes x 16 B per
+  // row, so that every 128-byte line is requested once; the place of a 16-byte piece inside its row of the
+  // tile (the bank swizzle) is expressed by which piece of the source row a lane asks for.
+  // Every load is unconditional: positions past the end of the list (in the last chunk, and in the chunk
+  // requested beyond the wave's last one) repeat the list's last key with an occupancy word of zero -- a
+  // listed key's rows are valid addresses, and with probabilities of exactly zero its finite V contributes
+  // nothing.  (The loop only runs when the list is not empty.)
+  const uint32_t my_row = (uint32_t)(lane >> 3), my_slot = (uint32_t)(lane & 7);
+  auto key_request = [&](int i, int slot) {                          // issue only
     const int kk = (wv + 4 * i) * KC + ql;
-    const bool ok = i < my_chunks && kk < list_len;
-    const int pos = list_begin + min(kk, list_len - 1);
-    const int k = idx[pos];
-    const uint32_t b = bits[pos];
-    key = ok ? k : -1;
-    bw = ok ? b : 0u;
+    const uint32_t pos = (uint32_t)(list_begin + min(kk, list_len - 1)) * 4u;
+    const uint32_t at = (uint32_t)(uintptr_t)(PIT_LDS char*)&s_list[wv][slot][0];
+    if (lane < KC) {
+      dma4(idx, pos, at);
+      dma4(bits, pos, at + KC * 4);
+    }
   };
-  // SRead: the K and V rows of a chunk (32 x 128 B each) are fetched whole, 8 lanes x 16 B per row, so
-  // that every 128-byte line is requested once; both go through LDS on their way to the operands.  A
-  // position without a key reads row 0 and gets zeros instead (its probabilities are zero, but 0 x Inf is not).
-  auto load_kv = [&](int key, uint4 (&kf)[4], uint4 (&vr)[4]) {
+  // (after the entries have landed) positions past the end of the list get an occupancy word of zero
+  auto key_finish = [&](int i, int slot) {
+    if (!(i < my_chunks && (wv + 4 * i) * KC + ql < list_len)) s_list[wv][slot][KC + ql] = 0u;
+    __builtin_amdgcn_wave_barrier();
+  };
+  // byte offset of this lane's row of the key tile, instruction `it` (tile rows 8 it + lane / 8)
+  auto row_offsets = [&](int slot, uint32_t (&ro)[4]) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) ro[it] = s_list[wv][slot][it * 8 + (int)my_row] * (uint32_t)(HD * 2);
+  };
+  auto request_v = [&](const uint32_t (&ro)[4], uint32_t v_lds) {
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int x = it * 64 + lane;
-      const int krow = __shfl(key, x >> 3);
-      const int64_t at = head_off + (int64_t)max(krow, 0) * HD + (x & 7) * 8;
-      const uint4 kq = *reinterpret_cast<const uint4*>(K + at);
-      const uint4 vq = *reinterpret_cast<const uint4*>(V + at);
-      const bool ok = krow >= 0;
-      kf[it] = make_uint4(ok ? kq.x : 0u, ok ? kq.y : 0u, ok ? kq.z : 0u, ok ? kq.w : 0u);
-      vr[it] = make_uint4(ok ? vq.x : 0u, ok ? vq.y : 0u, ok ? vq.z : 0u, ok ? vq.w : 0u);
+      const uint32_t r = (uint32_t)it * 8u + my_row;                    // v_off(r, c16) == r * 128 + 16 * my_slot
+      const uint32_t c16 = ((((my_slot >> 2) ^ ((r >> 1) & 1u)) << 2) | (my_slot & 3u));
+      dma16(v_head, ro[it] + c16 * 16u, v_lds + (uint32_t)it * 1024u);
+    }
+  };
+  // K tile [32 keys][8 pieces of 16 B], piece index XOR-ed with (key >> 1) & 7: the operand reads (lane: key
+  // ql, piece 2 ks + h) are free of bank conflicts
+  auto request_k = [&](const uint32_t (&ro)[4]) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const uint32_t r = (uint32_t)it * 8u + my_row;
+      dma16(k_head, ro[it] + ((my_slot ^ ((r >> 1) & 7u)) << 4), k_lds + (uint32_t)it * 1024u);
     }
   };
 
-  int key_a, key_b;
-  uint32_t bw_a, bw_b;
-  uint4 kf0[4], vr0[4], kf1[4], vr1[4];
-  key_a = key_b = -1;
-  bw_a = bw_b = 0u;
+  uint32_t ro[4];
   if (my_chunks > 0) {
-    load_key(0, key_a, bw_a);
-    load_key(1, key_b, bw_b);
-    load_kv(key_a, kf0, vr0);
+    key_request(0, 0);
+    key_request(1, 1);
+    wait_loads();
+    key_finish(0, 0);
+    key_finish(1, 1);
+    row_offsets(0, ro);
+    request_v(ro, v_lds0);
+    request_k(ro);
   }
-  // one chunk: key_a / bw_a belong to chunk i (rows in kf, vr), key_b / bw_b to chunk i + 1
-  auto step = [&](int i, uint4 (&kf)[4], uint4 (&vr)[4], uint4 (&kf_n)[4], uint4 (&vr_n)[4]) {
-    int key_c;
-    uint32_t bw_c;
-    load_key(i + 2, key_c, bw_c);
-    load_kv(key_b, kf_n, vr_n);
+  // one chunk; vb = i % 2.  On entry the rows of chunk i (V in tile vb, K) and the list entries of chunk i + 1
+  // (in slot vb ^ 1) were requested during the previous chunk.
+  auto step = [&](int i, int vb) {
+    const uint32_t v_lds = v_lds0 + (uint32_t)vb * V_TILE_BYTES;
+    wait_loads();                            // everything requested so far has landed
+    key_finish(i + 1, vb ^ 1);
+    row_offsets(vb ^ 1, ro);
+    wait_lds();                              // (the other V tile was read by the previous chunk)
+    request_v(ro, v_lds0 + (uint32_t)(vb ^ 1) * V_TILE_BYTES);
 
-    s_bits[wv][ql] = bw_a;               // (both halves of the wave hold the same word for query ql)
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int x = it * 64 + lane;
-      *(PIT_LDS u32x4_t*)(uintptr_t)(v_lds + v_off(x >> 3, x & 7)) = __builtin_bit_cast(u32x4_t, vr[it]);
-    }
-    // K tile [32 keys][8 chunks of 16 B], chunk index XOR-ed with (key >> 1) & 7: the straight writes
-    // and the operand reads (lane: key ql, chunk 2 ks + h) are both free of bank conflicts
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int x = it * 64 + lane;
-      const int r = x >> 3, c16 = x & 7;
-      *(PIT_LDS u32x4_t*)(uintptr_t)(k_lds + (uint32_t)(r * 128 + ((c16 ^ ((r >> 1) & 7)) << 4))) = __builtin_bit_cast(u32x4_t, kf[it]);
-    }
-    __builtin_amdgcn_wave_barrier();     // LDS writes above, LDS reads below: same wave, issued in order
     f32x16_t st;
 #pragma unroll
     for (int e = 0; e < 16; ++e) st[e] = 0.f;
+    u32x4_t ka[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const u32x4_t ka = *(PIT_LDS u32x4_t*)(uintptr_t)(k_lds + (uint32_t)(ql * 128 + (((2 * ks + h) ^ ((ql >> 1) & 7)) << 4)));
-      st = mfma_in<BF>(__builtin_bit_cast(uint4, ka), qf[ks], st);
-    }
+    for (int ks = 0; ks < 4; ++ks)
+      ka[ks] = *(PIT_LDS u32x4_t*)(uintptr_t)(k_lds + (uint32_t)(ql * 128 + (((2 * ks + h) ^ ((ql >> 1) & 7)) << 4)));
+    u32x4_t bwv[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      bwv[g] = *(PIT_LDS u32x4_t*)(uintptr_t)((uint32_t)(uintptr_t)(PIT_LDS char*)&s_list[wv][vb][KC + g * 8 + h * 4]);
+    wait_lds();                              // the K tile and this chunk's occupancy words are in registers:
+    request_k(ro);                           // the tile takes the next chunk's rows, the slot the list entries
+    key_request(i + 2, vb);                  // of the chunk after it
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) st = mfma_in<BF>(__builtin_bit_cast(uint4, ka[ks]), qf[ks], st);
     {
       // st[j] = S^T[key 8*(j/4) + 4*h + j%4][query ql]
       float mx = -INFINITY;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const u32x4_t bw = *(PIT_LDS u32x4_t*)(uintptr_t)((uint32_t)(uintptr_t)(PIT_LDS char*)&s_bits[wv][g * 8 + h * 4]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const bool on = (bw[e] >> ql) & 1u;
+          const bool on = (bwv[g][e] >> ql) & 1u;
           const float sc = on ? st[g * 4 + e] * scale_log2e : -INFINITY;
           st[g * 4 + e] = sc;
           mx = fmaxf(mx, sc);
@@ -268,14 +303,15 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
         }
       }
     }
-    __builtin_amdgcn_wave_barrier();     // the next chunk overwrites the tile just read
-    key_a = key_b; bw_a = bw_b;
-    key_b = key_c; bw_b = bw_c;
   };
-  for (int i = 0; i < my_chunks; i += 2) {      // the two row buffers alternate
-    step(i, kf0, vr0, kf1, vr1);
-    if (i + 1 < my_chunks) step(i + 1, kf1, vr1, kf0, vr0);
+  for (int i = 0; i < my_chunks; i += 2) {      // the two V tiles alternate
+    step(i, 0);
+    if (i + 1 < my_chunks) step(i + 1, 1);
   }
+  // the rows requested beyond the last chunk are still arriving in this wave's tiles, which now carry its
+  // partial result to wave 0
+  wait_loads();
+  wait_lds();
 
   // merge the 4 wavefronts' partial (m, l, O) per lane; wave 0 finishes
   if (wv > 0) {
