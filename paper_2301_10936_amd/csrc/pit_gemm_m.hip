@@ -322,34 +322,69 @@ k_gather_m_lds(const GemmArgs g) {
   }
 
   // ---------------------------------------------------------------- SWrite
+  // A lane holds one row of a 32 x 32 block, four columns per register quad; stored from there, one instruction
+  // would touch 32 rows with 32 bytes each -- 32 partial-line requests per instruction (the padded-batch product
+  // took 114 us that way, 99 us with whole lines).  So the wave's
+  // 32 x (32 WN) row blocks go through LDS (the ring is free now; each wave has a region of its own): written as
+  // the accumulators hold them, read back row-contiguous, and stored with 16 bytes per lane so that consecutive
+  // lanes fill whole 128-byte lines of the destination row.
+  constexpr int WCOLS = 32 * WN;                 // columns of the wave's tile
+  constexpr int PITCH = WCOLS + 4;               // floats per row in LDS: rows 16 bytes apart in the banks
+  static_assert(4 * 32 * PITCH * 4 <= NST * T::STAGE, "the four waves' row blocks must fit the ring");
+  __syncthreads();                               // every wave has read its last operands from the ring
+  float* cw = reinterpret_cast<float*>(smem) + wv * (32 * PITCH);
+  const int ql = lane & 31, hh = lane >> 5;
 #pragma unroll
   for (int i = 0; i < WM; ++i) {
-    const int r = wm * 32 * WM + i * 32 + (lane & 31);
-    const int64_t crow = s_rows_c[r];
-    if (crow < 0) continue;
-    float scale = 1.f;
-    if constexpr (EPI == EPI_STORE) { if (g.gate) scale = g.gate[crow]; }
+    const int rb = wm * 32 * WM + i * 32;        // first tile row of this row block
+    if (i >= live_i) break;                      // (uniform) no listed row in this block or the following ones
+    {
+      const int crow = s_rows_c[rb + ql];
+      float scale = 1.f;
+      if constexpr (EPI == EPI_STORE) { if (g.gate && crow >= 0) scale = g.gate[crow]; }
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
+      for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const int col = n0 + wn * 32 * WN + j * 32 + 8 * gq + 4 * (lane >> 5);
-        float v[4];
+        for (int gq = 0; gq < 4; ++gq) {
+          float v[4];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          v[x] = acc[i][j][4 * gq + x];
-          if constexpr (EPI == EPI_GELU) v[x] = gelu_erf_fast(v[x]);
-          if constexpr (EPI == EPI_STORE) v[x] *= scale;
+          for (int x = 0; x < 4; ++x) {
+            v[x] = acc[i][j][4 * gq + x];
+            if constexpr (EPI == EPI_GELU) v[x] = gelu_erf_fast(v[x]);
+            if constexpr (EPI == EPI_STORE) v[x] *= scale;
+          }
+          *reinterpret_cast<float4*>(cw + ql * PITCH + j * 32 + 8 * gq + 4 * hh) = make_float4(v[0], v[1], v[2], v[3]);
         }
-        if constexpr (CT == 0) {
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C) + crow * g.ldc + col) = make_float4(v[0], v[1], v[2], v[3]);
-        } else {
-          const uint32_t lo = (uint32_t)f32_to_in<BF>(v[0]) | ((uint32_t)f32_to_in<BF>(v[1]) << 16);
-          const uint32_t hi = (uint32_t)f32_to_in<BF>(v[2]) | ((uint32_t)f32_to_in<BF>(v[3]) << 16);
-          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.C) + crow * g.ldc + col) = make_uint2(lo, hi);
-        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    if constexpr (CT == 0) {
+      constexpr int LPR = WCOLS / 4, RPI = 64 / LPR;        // lanes per row, rows per store instruction
+      const int rr = lane / LPR, c4 = (lane % LPR) * 4;
+#pragma unroll
+      for (int t = 0; t < 32 / RPI; ++t) {
+        const int row = t * RPI + rr;
+        const int64_t crow = s_rows_c[rb + row];
+        const float4 v = *reinterpret_cast<const float4*>(cw + row * PITCH + c4);
+        if (crow >= 0) *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.C) + crow * g.ldc + n0 + wn * WCOLS + c4) = v;
+      }
+    } else {
+      constexpr int LPR = WCOLS / 8, RPI = 64 / LPR;
+      const int rr = lane / LPR, c8 = (lane % LPR) * 8;
+#pragma unroll
+      for (int t = 0; t < 32 / RPI; ++t) {
+        const int row = t * RPI + rr;
+        const int64_t crow = s_rows_c[rb + row];
+        const float4 a = *reinterpret_cast<const float4*>(cw + row * PITCH + c8);
+        const float4 b = *reinterpret_cast<const float4*>(cw + row * PITCH + c8 + 4);
+        uint4 pk;
+        pk.x = (uint32_t)f32_to_in<BF>(a.x) | ((uint32_t)f32_to_in<BF>(a.y) << 16);
+        pk.y = (uint32_t)f32_to_in<BF>(a.z) | ((uint32_t)f32_to_in<BF>(a.w) << 16);
+        pk.z = (uint32_t)f32_to_in<BF>(b.x) | ((uint32_t)f32_to_in<BF>(b.y) << 16);
+        pk.w = (uint32_t)f32_to_in<BF>(b.z) | ((uint32_t)f32_to_in<BF>(b.w) << 16);
+        if (crow >= 0) *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(g.C) + crow * g.ldc + n0 + wn * WCOLS + c8) = pk;
       }
     }
+    __builtin_amdgcn_wave_barrier();             // the next row block reuses the region
   }
 }
 
