@@ -434,6 +434,111 @@ k_bitmap_route(const int32_t* __restrict__ expert_id, int T, int E, int W, u64* 
 }
 
 // ----------------------------------------------------------------------------------------------
+// Routing decisions of up to 8192 tokens over up to 64 experts: the whole index in ONE launch by one workgroup
+// (a stable counting sort without atomics; the same lists as bitmap pass + ordered emit give).
+//   1. a wave takes 64 consecutive tokens; six ballots over the bits of the expert id give every lane the set
+//      of lanes with its expert, hence its rank among them and, in the first of them, their number:
+//      tab[chunk][expert]
+//   2. exclusive prefix of tab over the chunks (16 runs of chunks per expert, then the runs), totals per expert,
+//      exclusive prefix over the experts = seg_ptr
+//   3. token t goes to seg_ptr[e] + (tokens of e in earlier chunks) + (rank in its chunk)
+// Tokens with an id outside [0, E) are listed nowhere, counted in *status, and their rows of zero_rows (if given)
+// are cleared, as in k_bitmap_route.
+// ----------------------------------------------------------------------------------------------
+constexpr int ROUTE_ONE_MAX_T = 8192, ROUTE_ONE_CHUNKS = ROUTE_ONE_MAX_T / 64;
+__global__ void __launch_bounds__(1024)
+k_route_index_one(const int32_t* __restrict__ expert_id, int T, int E, int32_t* __restrict__ seg_ptr,
+                  int32_t* __restrict__ idx, int32_t* __restrict__ status,
+                  char* __restrict__ zero_rows, int64_t zero_ld_bytes, int zero_row_bytes) {
+  __shared__ int tab[ROUTE_ONE_CHUNKS][64];
+  __shared__ int run_sum[16][64];
+  __shared__ int base[64];
+  __shared__ int bad_s[16];
+  const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
+  for (int i = tid; i < ROUTE_ONE_CHUNKS * 64; i += 1024) (&tab[0][0])[i] = 0;
+  __syncthreads();
+  const int C = (T + 63) >> 6;
+  const int per = (C + 15) >> 4;                  // chunks per run; run g = chunks g * per .. g * per + per - 1
+  int my_e[ROUTE_ONE_CHUNKS / 16], my_rank[ROUTE_ONE_CHUNKS / 16];
+  int nbad = 0;
+#pragma unroll
+  for (int j = 0; j < ROUTE_ONE_CHUNKS / 16; ++j) {
+    const int c = wv + 16 * j;
+    my_e[j] = -1; my_rank[j] = 0;
+    if (c >= C) continue;                         // (uniform per wave)
+    const int t = c * 64 + ln;
+    const int e = t < T ? expert_id[t] : -1;
+    const bool valid = e >= 0 && e < E;
+    u64 bad = __ballot(t < T && !valid);
+    nbad += __builtin_popcountll(bad);
+    if (zero_rows != nullptr) {
+      while (bad) {
+        const int l = __builtin_ctzll(bad);
+        bad &= bad - 1;
+        char* row = zero_rows + (int64_t)(c * 64 + l) * zero_ld_bytes;
+        for (int b = ln * 16; b < zero_row_bytes; b += 64 * 16) *reinterpret_cast<uint4*>(row + b) = make_uint4(0, 0, 0, 0);
+      }
+    }
+    u64 same = __ballot(valid);
+#pragma unroll
+    for (int bit = 0; bit < 6; ++bit) {
+      const bool on = (e >> bit) & 1;
+      const u64 b = __ballot(on);
+      same &= on ? b : ~b;
+    }
+    const int rank = __builtin_popcountll(same & ((1ull << ln) - 1ull));
+    if (valid) {
+      my_e[j] = e; my_rank[j] = rank;
+      if (rank == 0) tab[c][e] = __builtin_popcountll(same);
+    }
+  }
+  if (ln == 0) bad_s[wv] = nbad;
+  __syncthreads();
+  {
+    const int e = ln, g = wv;                     // 16 waves = 16 runs of chunks, lane = expert
+    int sum = 0;
+    for (int c = g * per; c < min(C, (g + 1) * per); ++c) {
+      const int x = tab[c][e];
+      tab[c][e] = sum;
+      sum += x;
+    }
+    run_sum[g][e] = sum;
+  }
+  __syncthreads();
+  if (wv == 0) {
+    int total = 0;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      const int x = run_sum[g][ln];
+      run_sum[g][ln] = total;
+      total += x;
+    }
+    int inc = total;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int x = __shfl_up(inc, d);
+      if (ln >= d) inc += x;
+    }
+    base[ln] = inc - total;
+    if (ln < E) seg_ptr[ln] = inc - total;
+    if (ln == E - 1) seg_ptr[E] = inc;           // (experts beyond E have no tokens: total = 0 there)
+    if (ln == 0 && status != nullptr) {
+      int nb = 0;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) nb += bad_s[w];
+      *status = nb;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < ROUTE_ONE_CHUNKS / 16; ++j) {
+    const int c = wv + 16 * j;
+    const int e = my_e[j];
+    if (c < C && e >= 0) idx[base[e] + run_sum[c / per][e] + tab[c][e] + my_rank[j]] = c * 64 + ln;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
 // two-level counts (only used when there are many segments): cnt[s] = set bits of segment s,
 // blk[b] = set bits of segments 16 b .. 16 b + 15.  The start of segment s is then the sum of
 // blk[0 .. s / 16) and cnt[16 (s / 16) .. s): two short loads per workgroup instead of a scan pass.
@@ -892,7 +997,7 @@ static int launch_bitmap(const Layout& L, const void* d_src, int esize, int rows
   const int64_t row_bytes = (int64_t)cols * esize;
   const bool vec_ok = aligned(d_src, 16) && (ld * esize) % 16 == 0 && row_bytes % 16 == 0 && row_bytes < (1ll << 31);
   if (pit_dim == 0 && mt_rows == 1 && !want_bits && vec_ok && mt_bytes >= 16 && mt_bytes <= 1024 &&
-      (mt_bytes & (mt_bytes - 1)) == 0) {
+      (mt_bytes & (mt_bytes - 1)) == 0 && rows <= 65535 * 64) {          // (64 rows per workgroup, grid.y limit)
     const int lpm = (int)(mt_bytes / 16);
     dim3 grid((unsigned)ceil_div(row_bytes, 1024), (unsigned)ceil_div(rows, 64));
     if (esize == 1)      hipLaunchKernelGGL(k_bitmap_rows<1>, grid, dim3(256), 0, st, d_src, ld * esize, rows, (int)row_bytes, lpm, L.nseg, L.W, words);
@@ -1074,6 +1179,12 @@ int pit::launch_route_index(const int32_t* d_expert_id, int T, int E, const pit_
   char* ws = reinterpret_cast<char*>(d_ws);
   u64* words = reinterpret_cast<u64*>(ws);
   int32_t* cnt = reinterpret_cast<int32_t*>(ws + L.words_bytes);
+  if (T <= ROUTE_ONE_MAX_T && E <= 64) {
+    hipLaunchKernelGGL(k_route_index_one, dim3(1), dim3(1024), 0, st, d_expert_id, T, E, out->seg_ptr, out->idx, d_status,
+                       reinterpret_cast<char*>(zero_rows), zero_ld_bytes, zero_row_bytes);
+    PIT_LAUNCH_CHECK();
+    return PIT_OK;
+  }
   hipLaunchKernelGGL(k_bitmap_route, dim3((L.W + 3) / 4), dim3(256), 0, st, d_expert_id, T, E, L.W, words,
                      reinterpret_cast<char*>(zero_rows), zero_ld_bytes, zero_row_bytes);
   PIT_LAUNCH_CHECK();

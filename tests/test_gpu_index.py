@@ -214,7 +214,10 @@ def test_repeatable(pit):
     assert torch.equal(a.idx[:n], b.idx[:n])
 
 
-@pytest.mark.parametrize("T,E", [(4096, 64), (1000, 7), (63, 1), (300, 130), (1, 3)])
+# up to 8192 tokens and 64 experts the index is built by one workgroup in one launch; beyond, by the bitmap
+# pass and the ordered emit: (8192, 64) and (200, 64) are the largest and a small case of the first path,
+# (8200, 64), (9000, 16) and (300, 130) take the second
+@pytest.mark.parametrize("T,E", [(4096, 64), (1000, 7), (63, 1), (300, 130), (1, 3), (8192, 64), (200, 64), (8200, 64), (9000, 16)])
 def test_route_index(pit, T, E):
     w = wl.moe_ffn(T=T, d_model=8, d_ff=8, E=E, seed=T + E)
     eid = to_dev(w.expert_id)
@@ -237,6 +240,21 @@ def test_route_index_invalid_ids_and_empty(pit):
     ix = pit.pit_build_route_index(torch.empty(0, dtype=torch.int32, device=dev()), 4, status=status)
     torch.cuda.synchronize()
     assert ix.seg_ptr.cpu().tolist() == [0] * 5 and int(status[0]) == 0
+
+
+@pytest.mark.parametrize("T,E", [(5000, 20), (9000, 20)])
+def test_route_index_invalid_ids_on_both_paths(pit, T, E):
+    rng = np.random.default_rng(T)
+    eid_np = rng.integers(0, E, size=T).astype(np.int32)
+    badpos = rng.choice(T, size=37, replace=False)
+    eid_np[badpos] = rng.choice(np.array([-1, -5, E, E + 44, 64, 1 << 20], dtype=np.int32), size=37)
+    status = torch.zeros(1, dtype=torch.int32, device=dev())
+    ix = pit.pit_build_route_index(to_dev(eid_np), E, status=status)
+    torch.cuda.synchronize()
+    sp, idx, _ = ix.to_host()
+    rsp, ridx = orc.route_index(eid_np, E)
+    assert np.array_equal(sp, rsp) and np.array_equal(idx, ridx)
+    assert int(status[0]) == 37
 
 
 def test_error_returns(pit):
