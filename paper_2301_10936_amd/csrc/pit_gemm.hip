@@ -136,7 +136,7 @@ __device__ __forceinline__ void red_store(const f32x4_t (&acc)[JA][8], const Gem
         uint32_t w[4];
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-          w[x] = (uint32_t)f32_to_in<BF>(acc[ja][2 * x][e]) | ((uint32_t)f32_to_in<BF>(acc[ja][2 * x + 1][e]) << 16);
+          w[x] = pack2_in<BF>(acc[ja][2 * x][e], acc[ja][2 * x + 1][e]);
         __builtin_nontemporal_store(u32x4_t{w[0], w[1], w[2], w[3]},
                                     reinterpret_cast<u32x4_t*>(reinterpret_cast<uint16_t*>(g.C) + row * g.ldc + col));
       }

@@ -30,14 +30,28 @@ __device__ __forceinline__ uint16_t f32_to_f16_rne(float f) {
 template <bool BF> __device__ __forceinline__ uint16_t f32_to_in(float f) {
   return BF ? f32_to_bf16_rne(f) : f32_to_f16_rne(f);
 }
-// GELU(x) = x (1 + erf(x / sqrt 2)) / 2 with erf from the rational approximation 7.1.26 of Abramowitz & Stegun
-// (|error| <= 1.5e-7, far below the rounding of the result to bf16 / fp16): a fifth of the
-// instructions of erff; the GELU epilogue of the first MoE matmul is a quarter of its workgroups' run time otherwise.
+// Two fp32 values rounded (nearest-even) to the 16-bit input type and packed, a in the low half: one
+// v_cvt_pk_bf16_f32 on gfx950 for bf16 (the same rounding as f32_to_bf16_rne for every finite value and for
+// infinities; a NaN stays a NaN).
+typedef __bf16 pit_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 pit_f16x2_t __attribute__((ext_vector_type(2)));
+typedef float pit_f32x2_t __attribute__((ext_vector_type(2)));
+template <bool BF> __device__ __forceinline__ uint32_t pack2_in(float a, float b) {
+  const pit_f32x2_t v = {a, b};
+  if constexpr (BF) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, pit_bf16x2_t));
+  else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, pit_f16x2_t));
+}
+// GELU(x) = x (1 + erf(x / sqrt 2)) / 2 with erf(z) = 1 - 2^(-q(z)) for z >= 0, q the polynomial of degree 5 without
+// constant term fitted (weighted least squares, reweighted towards the minimax fit) to -log2(erfc z) on [0, 4.2];
+// beyond 4.2 q keeps growing (q >= 28.6 there: erfc itself is below 3e-9) until 2^-q underflows to zero.
+// |error of erf| <= 7e-7 in fp32, far below the rounding of the result to bf16 / fp16.  One transcendental
+// (v_exp_f32) and a dozen other instructions: half of the rational approximation 7.1.26 of Abramowitz & Stegun
+// (a reciprocal and an exponential), a tenth of erff -- the GELU epilogue of the first MoE matmul is a quarter of
+// its workgroups' run time with the library function.
 __device__ __forceinline__ float gelu_erf_fast(float x) {
   const float z = fabsf(x) * 0.70710678118654752f;
-  const float t = __frcp_rn(1.0f + 0.3275911f * z);
-  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  const float e = 1.0f - poly * __expf(-z * z);          // erf(|x| / sqrt 2)
+  const float q = z * (1.6278890371f + z * (0.9185093641f + z * (0.1486656219f + z * (-0.02959003858f + z * 0.00294415676f))));
+  const float e = 1.0f - __builtin_amdgcn_exp2f(-q);     // erf(|x| / sqrt 2)
   return 0.5f * x * (1.0f + copysignf(e, x));
 }
 

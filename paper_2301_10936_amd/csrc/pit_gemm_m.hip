@@ -377,10 +377,10 @@ k_gather_m_lds(const GemmArgs g) {
         const float4 a = *reinterpret_cast<const float4*>(cw + row * PITCH + c8);
         const float4 b = *reinterpret_cast<const float4*>(cw + row * PITCH + c8 + 4);
         uint4 pk;
-        pk.x = (uint32_t)f32_to_in<BF>(a.x) | ((uint32_t)f32_to_in<BF>(a.y) << 16);
-        pk.y = (uint32_t)f32_to_in<BF>(a.z) | ((uint32_t)f32_to_in<BF>(a.w) << 16);
-        pk.z = (uint32_t)f32_to_in<BF>(b.x) | ((uint32_t)f32_to_in<BF>(b.y) << 16);
-        pk.w = (uint32_t)f32_to_in<BF>(b.z) | ((uint32_t)f32_to_in<BF>(b.w) << 16);
+        pk.x = pack2_in<BF>(a.x, a.y);
+        pk.y = pack2_in<BF>(a.z, a.w);
+        pk.z = pack2_in<BF>(b.x, b.y);
+        pk.w = pack2_in<BF>(b.z, b.w);
         if (crow >= 0) *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(g.C) + crow * g.ldc + n0 + wn * WCOLS + c8) = pk;
       }
     }
