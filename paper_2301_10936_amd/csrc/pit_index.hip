@@ -455,19 +455,22 @@ k_route_index_one(const int32_t* __restrict__ expert_id, int T, int E, int32_t* 
   __shared__ int base[64];
   __shared__ int bad_s[16];
   const int tid = threadIdx.x, wv = tid >> 6, ln = tid & 63;
-  for (int i = tid; i < ROUTE_ONE_CHUNKS * 64; i += 1024) (&tab[0][0])[i] = 0;
-  __syncthreads();
   const int C = (T + 63) >> 6;
   const int per = (C + 15) >> 4;                  // chunks per run; run g = chunks g * per .. g * per + per - 1
   int my_e[ROUTE_ONE_CHUNKS / 16], my_rank[ROUTE_ONE_CHUNKS / 16];
   int nbad = 0;
+  // all of this wave's expert ids are requested before the first is used (unconditional loads at clamped
+  // positions: one round trip to memory instead of one per chunk)
+  int raw[ROUTE_ONE_CHUNKS / 16];
+#pragma unroll
+  for (int j = 0; j < ROUTE_ONE_CHUNKS / 16; ++j) raw[j] = expert_id[min((wv + 16 * j) * 64 + ln, T - 1)];
 #pragma unroll
   for (int j = 0; j < ROUTE_ONE_CHUNKS / 16; ++j) {
     const int c = wv + 16 * j;
     my_e[j] = -1; my_rank[j] = 0;
     if (c >= C) continue;                         // (uniform per wave)
     const int t = c * 64 + ln;
-    const int e = t < T ? expert_id[t] : -1;
+    const int e = t < T ? raw[j] : -1;
     const bool valid = e >= 0 && e < E;
     u64 bad = __ballot(t < T && !valid);
     nbad += __builtin_popcountll(bad);
@@ -487,6 +490,8 @@ k_route_index_one(const int32_t* __restrict__ expert_id, int T, int E, int32_t* 
       same &= on ? b : ~b;
     }
     const int rank = __builtin_popcountll(same & ((1ull << ln) - 1ull));
+    tab[c][ln] = 0;                               // (this wave owns row c of the table)
+    __builtin_amdgcn_wave_barrier();
     if (valid) {
       my_e[j] = e; my_rank[j] = rank;
       if (rank == 0) tab[c][e] = __builtin_popcountll(same);
