@@ -304,7 +304,7 @@ size_t pit_moe_workspace(int T, int d_model, int d_ff, int E);
  *   d_X   [T x d_model] in_dt, row-major, contiguous.     d_Y  [T x d_model] y_dt (PIT_F32/BF16/F16).
  *   d_W1  [E][d_model][d_ff] in_dt, contiguous.            d_W2 [E][d_ff][d_model] in_dt, contiguous.
  *   d_gate [T] fp32 or NULL (= 1).    act: 0 = erf-form GELU x (1 + erf(x / sqrt 2)) / 2 (erf evaluated
- *   to 1.5e-7 absolute error, below the rounding of the hidden row to the input type), 1 = identity.
+ *   to 7e-7 absolute error, below the rounding of the hidden row to the input type), 1 = identity.
  *   The hidden activations are kept in in_dt (rounded nearest-even) between the two matmuls.
  *   d_status (may be NULL): set to the number of tokens whose expert id is outside [0, E); those
  *   tokens' rows of Y are zero.
@@ -331,8 +331,10 @@ size_t pit_sparse_attn_workspace(int H, int S, int D);
  *           micro-tile the element mask is honoured exactly.  A query with no allowed key gives a
  *           zero row.
  * Precision: scores, softmax and accumulation in fp32.  V enters the second product in its own type
- * (every finite bf16 / fp16 value as it is: no range restriction); the softmax numerators enter it as
- * a two-term bf16 sum (relative error < 2^-15) for bf16 inputs and rounded to fp16 for fp16 inputs.
+ * (every finite bf16 / fp16 value as it is: no range restriction; K and V must be finite in the rows of
+ * listed keys -- a key that some query of a block attends to meets the other 31 queries with a
+ * probability of exactly zero, and 0 x Inf is not 0); the softmax numerators enter it as a two-term
+ * bf16 sum (relative error < 2^-15) for bf16 inputs and rounded to fp16 for fp16 inputs.
  * Shape rules: D == 64, S % 32 == 0.
  */
 int pit_sparse_attn(const void* d_Q, const void* d_K, const void* d_V, const uint8_t* d_mask,
