@@ -376,83 +376,91 @@ k_sparse_attn(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, co
 // kernel is the only reader of this index, so the list of every query block may sit at a fixed place,
 // qb * S, with its length beside it; no prefix over the blocks is needed and one workgroup can do
 // detection, scan and ordered emit for its block without waiting for any other.
-// A thread owns 16 consecutive keys and loads them for the 32 queries of the block (16 B per row, a
-// wave reads 1 KiB of a mask row at a time); the non-zero test runs on four bytes at once and leaves,
-// per group of 8 queries, a byte of occupancy bits per key; four such bytes make the key's word.
+// A thread owns 16 consecutive keys and 8 of the block's 32 queries (16 B per row, a wave reads 1 KiB of
+// a mask row at a time); the non-zero test runs on four bytes at once and leaves a byte of occupancy
+// bits per key; the four bytes of a key (one per group of 8 queries) make the key's word.
 // Entries are written in ascending key order: threads, waves and passes of 4096 keys are in key order
 // and positions come from an exclusive scan of the per-thread counts.
 // ----------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(1024)
 k_mask_index_q32(const uint8_t* __restrict__ mask, int S, int32_t* __restrict__ cnt,
                  int32_t* __restrict__ idx, uint32_t* __restrict__ bits) {
+  // 4 groups of 256 threads: group g tests queries 8 g .. 8 g + 7 for the 16 keys of thread tid % 256 (8 loads per
+  // thread: the 16 waves of the workgroup have the whole 128 KiB of a pass under way at once); the groups' bytes
+  // of occupancy bits meet in LDS, and the first group makes the words, scans and writes the list.
+  __shared__ uint4 s_part[3][256];
   __shared__ int s_wave[4];
-  const int qb = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const uint8_t* base = mask + (int64_t)qb * QB * S;
+  const int qb = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const int grp = tid >> 8, ct = tid & 255, wv = ct >> 6;
+  const uint8_t* base = mask + (int64_t)qb * QB * S + (int64_t)(8 * grp) * S;
   int32_t* out_i = idx + (int64_t)qb * S;
   uint32_t* out_b = bits + (int64_t)qb * S;
   int run = 0;                                    // entries written by earlier passes (uniform)
   for (int c_base = 0; c_base < S; c_base += 4096) {
-    const int c0 = c_base + tid * 16;
-    uint32_t acc[4][4];                           // [group of 8 queries][4 keys]: byte j = the 8 queries' bits of key 4 w + j
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int w = 0; w < 4; ++w) acc[q][w] = 0;
+    const int c0 = c_base + ct * 16;
+    uint32_t acc[4] = {0u, 0u, 0u, 0u};           // [4 keys]: byte j = the group's 8 queries' bits of key 4 w + j
     if (c0 < S) {
+      uint4 v[8];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        uint4 v[8];
+      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4*>(base + (int64_t)i * S + c0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint4*>(base + (int64_t)(8 * q + i) * S + c0);
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t d[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const uint32_t d[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            // bit 7 of every non-zero byte, moved to bit i of that byte
-            const uint32_t nz = (((d[w] & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | d[w]) & 0x80808080u;
-            acc[q][w] |= nz >> (7 - i);
-          }
+        for (int w = 0; w < 4; ++w) {
+          // bit 7 of every non-zero byte, moved to bit i of that byte
+          const uint32_t nz = (((d[w] & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | d[w]) & 0x80808080u;
+          acc[w] |= nz >> (7 - i);
         }
       }
     }
-    uint32_t o[16];
-    uint32_t flags = 0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int w = j >> 2;
-      const uint32_t b = (uint32_t)(j & 3);
-      // byte b of the four groups' words -> bytes 0..3 of the key's occupancy word (selector 0x0c = zero byte)
-      const uint32_t lo = __builtin_amdgcn_perm(acc[1][w], acc[0][w], 0x0c0c0000u | ((4u + b) << 8) | b);
-      const uint32_t hi = __builtin_amdgcn_perm(acc[3][w], acc[2][w], 0x00000c0cu | ((4u + b) << 24) | (b << 16));
-      o[j] = lo | hi;
-      flags |= (o[j] != 0 ? 1u : 0u) << j;
-    }
-    const int mine = __builtin_popcount(flags);
-    int inc = mine;
-#pragma unroll
-    for (int dd = 1; dd < 64; dd <<= 1) {
-      const int t = __shfl_up(inc, dd);
-      if (lane >= dd) inc += t;
-    }
-    if (lane == 63) s_wave[wv] = inc;
+    if (grp > 0) s_part[grp - 1][ct] = make_uint4(acc[0], acc[1], acc[2], acc[3]);
     __syncthreads();
-    int pos = run + inc - mine, total = 0;
+    uint32_t o[16];
+    int mine = 0, inc = 0;
+    if (grp == 0) {
+      const uint4 p1 = s_part[0][ct], p2 = s_part[1][ct], p3 = s_part[2][ct];
+      const uint32_t a1[4] = {p1.x, p1.y, p1.z, p1.w}, a2[4] = {p2.x, p2.y, p2.z, p2.w}, a3[4] = {p3.x, p3.y, p3.z, p3.w};
+      uint32_t flags = 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int w = j >> 2;
+        const uint32_t b = (uint32_t)(j & 3);
+        // byte b of the four groups' words -> bytes 0..3 of the key's occupancy word (selector 0x0c = zero byte)
+        const uint32_t lo = __builtin_amdgcn_perm(a1[w], acc[w], 0x0c0c0000u | ((4u + b) << 8) | b);
+        const uint32_t hi = __builtin_amdgcn_perm(a3[w], a2[w], 0x00000c0cu | ((4u + b) << 24) | (b << 16));
+        o[j] = lo | hi;
+        flags |= (o[j] != 0 ? 1u : 0u) << j;
+      }
+      mine = __builtin_popcount(flags);
+      inc = mine;
+#pragma unroll
+      for (int dd = 1; dd < 64; dd <<= 1) {
+        const int t = __shfl_up(inc, dd);
+        if (lane >= dd) inc += t;
+      }
+      if (lane == 63) s_wave[wv] = inc;
+    }
+    __syncthreads();
+    int total = 0;
+    int pos = run + inc - mine;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const int x = s_wave[w];
       if (w < wv) pos += x;
       total += x;
     }
+    if (grp == 0) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if (o[j] != 0) {
-        out_i[pos] = c0 + j;
-        out_b[pos] = o[j];
-        ++pos;
-      }
+      for (int j = 0; j < 16; ++j)
+        if (o[j] != 0) {
+          out_i[pos] = c0 + j;
+          out_b[pos] = o[j];
+          ++pos;
+        }
+    }
     run += total;
-    __syncthreads();                              // s_wave is rewritten by the next pass
+    __syncthreads();                              // s_wave and s_part are rewritten by the next pass
   }
   if (tid == 0) cnt[qb] = run;
 }
@@ -511,7 +519,7 @@ extern "C" int pit_sparse_attn(const void* d_Q, const void* d_K, const void* d_V
   int list_stride = 0;
   if (aligned(d_mask, 16) && (int64_t)L.nseg * S < (1ll << 31)) {
     list_stride = S;
-    hipLaunchKernelGGL(k_mask_index_q32, dim3((unsigned)L.nseg), dim3(256), 0, st, d_mask, S, ix.seg_ptr, ix.idx, ix.bits);
+    hipLaunchKernelGGL(k_mask_index_q32, dim3((unsigned)L.nseg), dim3(1024), 0, st, d_mask, S, ix.seg_ptr, ix.idx, ix.bits);
     PIT_LAUNCH_CHECK();
   } else {
     const int rc = pit_build_index(d_mask, PIT_U8, S, S, S, QB, 1, 1, &ix, ws + L.build_off, L.total - L.build_off, stream);
