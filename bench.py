@@ -102,6 +102,34 @@ def _read_traffic(name):
     return None
 
 
+def _mfma_issue_rates():
+    """Register-resident issue rate of the two MFMA shapes the kernels use, measured in this run with the probe
+    library (built next to the product library; None if it is not there): TFLOP/s over the chip at 1 and at 4
+    waves per SIMD.  Context for the nominal peak the roofline is priced against."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "paper_2301_10936_amd", "libpit_probe.so")
+    if not os.path.exists(path):
+        return None
+    lib = ctypes.CDLL(path)
+    lib.pit_probe_mfma.restype = ctypes.c_double
+    lib.pit_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    out = torch.zeros(4, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    res = {}
+    for shape, name in ((0, "16x16x32_bf16"), (1, "32x32x16_bf16")):
+        for wps in (1, 4):
+            flops = [0.0]
+
+            def run():
+                flops[0] = lib.pit_probe_mfma(shape, cus * wps, 20000, out.data_ptr(), st)
+
+            sec = _group_time(run, groups=2, per_group=3)
+            res[f"{name}_at_{wps}_waves_per_simd"] = round(flops[0] / sec / 1e12, 1)
+    return res
+
+
 # --------------------------------------------------------------------------------------------------
 def bench_relu_ffn(pit, wl, steps, warmup, pool=8, with_cpu=True, with_identity=True):
     import numpy as np
@@ -609,6 +637,13 @@ def main():
                      "traffic_source": "profiles/k_gather_k_direct_relu_ffn.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a committed run, not measured in this run)"},
         "paper_context": "paper reports up to 5.9x (avg 2.43x) over compilers on A100/V100 end-to-end; no TFLOP/s figure",
     }
+    try:
+        rates = _mfma_issue_rates()
+    except Exception:  # the probe is context, never a reason to lose the headline
+        rates = None
+    if rates:
+        line["mfma_issue_rate_measured_TFLOPs"] = rates
+        line["roofline"]["frac_of_measured_rate_of_its_mfma_shape"] = round(gemm_tflops / rates["16x16x32_bf16_at_4_waves_per_simd"], 4)
     if "cpu" in r:
         line["cpu_baseline"] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in r["cpu"].items()}
     if not args.only_headline:
