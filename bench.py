@@ -216,6 +216,10 @@ def bench_relu_ffn(pit, wl, steps, warmup, pool=8, with_cpu=True, with_identity=
         "step_event_ms_p10_p50_p90": [round(float(np.percentile(step_ev, q)), 4) for q in (10, 50, 90)],
         "gemm_kernel_ms": kernel_ms, "gemm_kernel_flops": eff_flops[last], "gemm_kernel_identity_index_ms": ident_ms, "gemm_kernel_interleaved_ms": real_ms,
         "dense_ms": float(dense_ms), "dense_flops": 2.0 * M * K * N,
+        # bookkeeping of the same workload at the other granularities: non-zero elements, and what the 128-token
+        # tile of the kernel actually multiplies (its cover of the 32 x 1 pattern)
+        "flops_nonzero_elements": float(np.mean([2.0 * int(((w.Xt & 0x7FFF) != 0).sum()) * N for w in ws])),
+        "flops_covered_by_128_token_tiles": float(np.mean([2.0 * _count_nonzero_microtiles(w.Xt, 128) * 128 * N for w in ws])),
     }
     if with_cpu:
         res["cpu"] = _cpu_oracle_leg(ws, eff_flops, MT)
@@ -621,6 +625,10 @@ def main():
                                "from a pool of 8 activations; effective FLOPs counted on non-zero 32x1 micro-tiles",
                    "M": 2048, "K": 8192, "N": 2048, "dense_tile": "128x128x32 per wave, 4-wave split of the k-list", "index_microtile": "128x1"},
         "frac_mfma_peak": round(value / MFMA_PEAK_TFLOPS, 4),
+        "gflop_per_step": {"non_zero_32x1_micro_tiles (counted in value)": round(r["eff_flops"] / 1e9, 2),
+                           "non_zero_elements": round(r["flops_nonzero_elements"] / 1e9, 2),
+                           "multiplied_by_the_128_token_tiles": round(r["flops_covered_by_128_token_tiles"] / 1e9, 2),
+                           "dense": round(r["dense_flops"] / 1e9, 2)},
         "speedup_vs_dense": round(r["dense_ms"] / (sec * 1e3), 3),
         "dense_gemm_ms": round(r["dense_ms"], 4),
         "index_build_ms": round(r["index_ms"], 4), "gemm_ms": round(r["gemm_ms"], 4),
