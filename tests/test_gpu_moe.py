@@ -28,7 +28,11 @@ def _run(pit, w, act=0, gate=True, y_dtype=torch.float32, sentinel=None):
     return Y, int(status[0])
 
 
-@pytest.mark.parametrize("T,d_model,d_ff,E", [(64, 128, 128, 2), (300, 128, 256, 5), (1000, 256, 384, 16), (129, 128, 128, 1)])
+# (2000, .., 100): more than 64 experts -- the tile lookup of the product kernel scans the segments in two passes and
+# the route index takes the bitmap + emit path; (9000, .., 70): more tokens than the one-launch route index takes;
+# (20000, 128, 256, 100): enough row tiles for the 128 x 256 tile of the product kernel with more than 64 segments
+@pytest.mark.parametrize("T,d_model,d_ff,E", [(64, 128, 128, 2), (300, 128, 256, 5), (1000, 256, 384, 16), (129, 128, 128, 1),
+                                              (2000, 128, 256, 100), (9000, 128, 128, 70), (20000, 128, 256, 100)])
 def test_exact_on_integers_identity_activation(pit, T, d_model, d_ff, E):
     """Both matmuls, the gather and the scatter, with nothing left to tolerance."""
     w = wl.moe_ffn(T=T, d_model=d_model, d_ff=d_ff, E=E, seed=T, integer=True, unit_gate=True)
