@@ -24,8 +24,8 @@
 // Precision of P in the second product: P rounded to bf16 would by itself cost about 1.7e-3 relative
 // Frobenius error.  With fp16 inputs P is rounded to fp16 (11-bit significand, 4 MFMAs per chunk).
 // With bf16 inputs V stays bf16 -- every finite bf16 value is used as it is, no range restriction --
-// and P enters as the sum of two bf16 terms, P = hi + lo with hi = P truncated to bf16 and lo = the
-// exact fp32 remainder rounded to bf16 (relative error of the pair below 2^-15), in 8 MFMAs per chunk
+// and P enters as the sum of two bf16 terms, P = hi + lo with hi = P rounded to bf16 and lo = the
+// exact fp32 remainder rounded to bf16 (relative error of the pair below 2^-17), in 8 MFMAs per chunk
 // that share their V operands.
 #include "pit_common.hpp"
 
@@ -55,14 +55,15 @@ __device__ __forceinline__ uint32_t pack_f16x2(float a, float b) {
   const uint16_t lo = __builtin_bit_cast(uint16_t, (_Float16)a), hi = __builtin_bit_cast(uint16_t, (_Float16)b);
   return (uint32_t)lo | ((uint32_t)hi << 16);
 }
-// a, b >= 0 (softmax numerators).  hi2 = {a, b} truncated to bf16; lo2 = the remainders a - hi(a), b - hi(b)
-// (exact in fp32) rounded to bf16 (half up on the magnitude; they are >= 0).  hi + lo reproduces the fp32
-// value to 2^-15 relative.
+// hi2 = {a, b} rounded to bf16 (nearest even, one v_cvt_pk_bf16_f32); lo2 = the remainders a - hi(a), b - hi(b)
+// (exact in fp32, of either sign) rounded to bf16 the same way.  hi + lo reproduces the fp32 value to 2^-17 relative.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t& hi2, uint32_t& lo2) {
-  const uint32_t ua = __builtin_bit_cast(uint32_t, a), ub = __builtin_bit_cast(uint32_t, b);
-  hi2 = __builtin_amdgcn_perm(ub, ua, 0x07060302u);
-  const float ra = a - __builtin_bit_cast(float, ua & 0xFFFF0000u), rb = b - __builtin_bit_cast(float, ub & 0xFFFF0000u);
-  lo2 = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, rb) + 0x8000u, __builtin_bit_cast(uint32_t, ra) + 0x8000u, 0x07060302u);
+  const f32x2_t v = {a, b};
+  hi2 = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+  const f32x2_t r = {a - __builtin_bit_cast(float, hi2 << 16), b - __builtin_bit_cast(float, hi2 & 0xFFFF0000u)};
+  lo2 = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, bf16x2_t));
 }
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
