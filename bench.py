@@ -8,6 +8,10 @@ HBM.  The headline workload is the ReLU-activation-sparse FFN down-projection
 every step from a pool of 8 different activations, and the product runs over the listed
 micro-tiles only.
 
+Every timed region, the dense comparators' included, is preceded by 60 ms of the same work run back to back
+(see _sustain): the GPU reaches the clocks of sustained load only after tens of milliseconds, and a figure taken
+during that ramp is neither reproducible nor what a serving loop sees.
+
 One JSON line is printed.  `value` is effective TFLOP/s: 2 * (elements of non-zero 32x1
 micro-tiles of X) * N divided by the wall time of a step (index build included).
 `roofline` is for the dominant kernel (the SRead/MFMA/SWrite GEMM) with its duration measured by
@@ -49,9 +53,46 @@ def _count_nonzero_microtiles(bits_u16, mt):
     return int(nz.reshape(nz.shape[0], nz.shape[1] // mt, mt).any(axis=2).sum())
 
 
-def _time_steps(step, steps, warmup):
-    """Run `warmup` untimed and `steps` timed calls of step(i); returns seconds per step (wall, synchronised)."""
+SUSTAIN_S = 0.06     # seconds of untimed, back-to-back work in front of every timed region
+
+
+def _sustain(step, seconds=SUSTAIN_S):
+    """Untimed.  The GPU reaches the clocks of sustained load only after tens of milliseconds of uninterrupted work
+    (measured on the headline step after a second of idling: 160, 81, 74, 74, 72, 71, 70, 69, 69, 68 us per step in
+    consecutive blocks of 50 steps, 67.5-68 us from step 500 on; the dense library GEMM ramps the same way, 96 ->
+    79 us).  A short warm-up therefore times the ramp, differently for every workload and comparator, and what it
+    reports is neither reproducible nor what a serving or training loop sees.  So every timed region in this file,
+    the dense comparators' included, is preceded by `seconds` of the same work, run back to back."""
     import torch
+    t0 = time.perf_counter()
+    i = 0
+    while True:
+        for _ in range(32):
+            step(i)
+            i += 1
+        torch.cuda.synchronize()
+        if time.perf_counter() - t0 >= seconds:
+            return
+
+
+def _time_call(fn, reps, seconds=SUSTAIN_S):
+    """Milliseconds per call of fn() between two events, `reps` back-to-back calls after the sustain phase."""
+    import torch
+    _sustain(lambda i: fn(), seconds)
+    e = _events(2)
+    e[0].record()
+    for _ in range(reps):
+        fn()
+    e[1].record()
+    torch.cuda.synchronize()
+    return e[0].elapsed_time(e[1]) / reps
+
+
+def _time_steps(step, steps, warmup):
+    """The sustain phase, then `warmup` untimed and `steps` timed calls of step(i); returns seconds per step
+    (wall, synchronised on both sides)."""
+    import torch
+    _sustain(step)
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -66,6 +107,7 @@ def _group_time(fn, groups=4, per_group=8):
     """Seconds per call of fn() from groups of back-to-back calls between two events (an event pair around one
     launch would also measure the dispatch gap)."""
     import torch
+    _sustain(lambda i: fn(), SUSTAIN_S / 2)
     for _ in range(3):
         fn()
     ev = _events(2 * groups)
@@ -201,15 +243,7 @@ def bench_relu_ffn(pit, wl, steps, warmup, pool=8, with_cpu=True, with_identity=
 
     # dense comparator at the same shape: hipBLASLt through torch.matmul on a row-major copy of X
     X = Xts[0].t().contiguous()
-    for _ in range(5):
-        torch.matmul(X, W)
-    e = _events(2)
-    e[0].record()
-    for _ in range(20):
-        torch.matmul(X, W)
-    e[1].record()
-    torch.cuda.synchronize()
-    dense_ms = e[0].elapsed_time(e[1]) / 20
+    dense_ms = _time_call(lambda: torch.matmul(X, W), 50)
 
     res = {
         "sec_per_step": sec, "eff_flops": eff, "index_ms": float(idx_ms), "gemm_ms": float(gemm_ms),
@@ -287,16 +321,9 @@ def bench_relu_ffn_correlated(pit, wl, steps, warmup, pool=4, live_block=128, li
     sec_sel = _time_steps(lambda i: pit.pit_select_and_run_gemm(cands, num, grid, Xts[i % pool], W, M, N, K, out=C, ws=wsel),
                           steps, warmup)
     X = Xts[0].t().contiguous()
-    for _ in range(3):
-        torch.matmul(X, W)
-    e = _events(2)
-    e[0].record()
-    for _ in range(10):
-        torch.matmul(X, W)
-    e[1].record()
-    torch.cuda.synchronize()
+    dense_ms = _time_call(lambda: torch.matmul(X, W), 30)
     names = ["gather_k_128", "gather_k_64", "gather_k_32", "dense_k"]
-    return {"sec_per_step": by_mt[128], "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 10,
+    return {"sec_per_step": by_mt[128], "eff_flops": eff, "dense_ms": dense_ms,
             "extra": {"ms_per_step_by_tile_height": {str(k): round(v * 1e3, 4) for k, v in by_mt.items()},
                       "algorithm1_selected": names[chosen], "ms_per_step_selected": round(sec_sel * 1e3, 4)}}
 
@@ -418,18 +445,11 @@ def bench_padded_linear(pit, wl, steps, warmup, pool=4):
         pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Yb, zero_uncovered=True)
 
     sec_bf = _time_steps(step_bf16, steps, warmup)
-    e = _events(2)
-    for _ in range(3):
-        torch.matmul(X, W)
-    e[0].record()
-    for _ in range(10):
-        torch.matmul(X, W)
-    e[1].record()
-    torch.cuda.synchronize()
+    dense_ms = _time_call(lambda: torch.matmul(X, W), 30)
     # the product kernel alone on the last index (no index build, no clearing of the padding rows)
     rows = int(ws[(warmup + steps - 1) % pool].lengths.sum())
     k_s = _group_time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Y, zero_uncovered=False))
-    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 10, "dense_flops": 2.0 * M * K * N,
+    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": dense_ms, "dense_flops": 2.0 * M * K * N,
             "extra": {"padding_rows_left_untouched_ms_per_step": round(sec_nz * 1e3, 4),
                       "bf16_output_ms_per_step": round(sec_bf * 1e3, 4), "gemm_kernel_ms": round(k_s * 1e3, 4),
                       "dense_comparator": "hipBLASLt bf16 GEMM over all 16384 rows, bf16 output (this path: fp32 output, padding rows cleared)",
@@ -455,19 +475,12 @@ def bench_microtile(pit, wl, steps, warmup, pool=8):
         pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, A, B, ix, 32, M, N, K, out=C)
 
     sec = _time_steps(step, steps, warmup)
-    e = _events(2)
-    for _ in range(5):
-        torch.matmul(As[0], B)
-    e[0].record()
-    for _ in range(20):
-        torch.matmul(As[0], B)
-    e[1].record()
-    torch.cuda.synchronize()
+    dense_ms = _time_call(lambda: torch.matmul(As[0], B), 50)
     # the strip kernel alone; its algorithmic bytes: the kept micro-tiles of A, B and C once each (a launch of
     # this size is bound by launch and first-load latency, not by any throughput)
     k_s = _group_time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, As[0], B, ix, 32, M, N, K, out=C))
     alg_bytes = float(ws[0].keep.sum()) * 64 + K * N * 2 + M * N * 4
-    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 20, "dense_flops": 2.0 * M * K * N,
+    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": dense_ms, "dense_flops": 2.0 * M * K * N,
             "extra": {"gemm_kernel_ms": round(k_s * 1e3, 4),
                       "roofline": _roofline("hbm", alg_bytes / k_s / 1e9, "k_slab_strip (f16)", "latency-bound at this size: three dependent launches of 3-14 us")}}
 
@@ -493,19 +506,12 @@ def bench_moe(pit, wl, steps, warmup, pool=4):
     # dense comparator: what capacity-padded batched matmul does -- every expert padded to the busiest one
     cap = int(max(np.bincount(r.expert_id, minlength=E).max() for r in routes))
     Xp = torch.zeros((E, cap, d_model), dtype=torch.bfloat16, device="cuda")
-    e = _events(2)
-    for _ in range(2):
-        torch.bmm(torch.nn.functional.gelu(torch.bmm(Xp, W1)), W2)
-    e[0].record()
-    for _ in range(5):
-        torch.bmm(torch.nn.functional.gelu(torch.bmm(Xp, W1)), W2)
-    e[1].record()
-    torch.cuda.synchronize()
+    dense_ms = _time_call(lambda: torch.bmm(torch.nn.functional.gelu(torch.bmm(Xp, W1)), W2), 10)
     weight_bytes = 2.0 * (W1.numel() + W2.numel())
     # a dense FFN with the same FLOPs: all T tokens through ONE expert's weights (what the layer would cost without routing)
     Xd = X
     same_s = _group_time(lambda: torch.matmul(torch.nn.functional.gelu(torch.matmul(Xd, W1[0])), W2[0]), 2, 4)
-    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 5,
+    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": dense_ms,
             "dense_flops": 4.0 * E * cap * d_model * d_ff, "hbm_floor_bytes": weight_bytes,
             "extra": {"dense_comparator": "capacity-padded batched matmul (every expert padded to the busiest one)",
                       "dense_ffn_same_flops_one_expert_ms": round(same_s * 1e3, 4),
@@ -531,14 +537,7 @@ def bench_attn(pit, wl, steps, warmup, pool=4):
 
     sec = _time_steps(step, steps, warmup)
     bias = torch.where(masks[0] != 0, 0.0, float("-inf")).to(torch.bfloat16)
-    e = _events(2)
-    for _ in range(2):
-        torch.softmax(torch.baddbmm(bias, Q, K.transpose(1, 2), alpha=scale).float(), dim=-1).to(torch.bfloat16) @ V
-    e[0].record()
-    for _ in range(5):
-        torch.softmax(torch.baddbmm(bias, Q, K.transpose(1, 2), alpha=scale).float(), dim=-1).to(torch.bfloat16) @ V
-    e[1].record()
-    torch.cuda.synchronize()
+    dense_ms = _time_call(lambda: torch.softmax(torch.baddbmm(bias, Q, K.transpose(1, 2), alpha=scale).float(), dim=-1).to(torch.bfloat16) @ V, 10)
     extra = {"dense_comparator": "unfused torch baddbmm + fp32 softmax + matmul with an additive mask",
              "gathered_KV_GB_per_s": round(2.0 * H * kept * D * 2 / sec / 1e9, 1),
              "roofline": _roofline("mfma", eff / sec / 1e12, "pit_sparse_attn (index of the mask + k_sparse_attn)",
@@ -550,7 +549,7 @@ def bench_attn(pit, wl, steps, warmup, pool=4):
         extra["fused_sdpa_dense_ms"] = round(_group_time(lambda: f(Q, K, V, attn_mask=bm, scale=scale), 2, 4) * 1e3, 4)
     except Exception as ex:
         extra["fused_sdpa_dense_ms"] = f"unavailable: {type(ex).__name__}"
-    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": e[0].elapsed_time(e[1]) / 5, "dense_flops": 4.0 * H * S * S * D, "extra": extra}
+    return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": dense_ms, "dense_flops": 4.0 * H * S * S * D, "extra": extra}
 
 
 def _summary(r):

@@ -26,10 +26,13 @@ MTS = (128, 64, 32)
 
 
 def _time(fn, reps):
-    for _ in range(3):
-        fn()
-    torch.cuda.synchronize()
-    time.sleep(0.02)          # every measurement starts from the same idle state of the clocks
+    # the clocks of sustained load are reached only after tens of milliseconds of uninterrupted work (the first
+    # few hundred launches after an idle spell run 10-20 % slower): what is timed is preceded by 50 ms of itself
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.05:
+        for _ in range(16):
+            fn()
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
