@@ -64,8 +64,10 @@ def _sustain(step, seconds=SUSTAIN_S):
     reports is neither reproducible nor what a serving or training loop sees.  So every timed region in this file,
     the dense comparators' included, is preceded by `seconds` of the same work, run back to back."""
     import torch
+    step(0)                       # (one-time set-up behind a first call, e.g. the library GEMM's, is not sustained work)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    i = 0
+    i = 1
     while True:
         for _ in range(32):
             step(i)

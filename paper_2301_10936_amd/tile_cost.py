@@ -39,6 +39,8 @@ def _dev(bits):
 def _time(fn, reps=20):
     # the clocks of sustained load are reached only after tens of milliseconds of uninterrupted work (the first
     # few hundred launches after an idle spell run 10-20 % slower): what is timed is preceded by 50 ms of itself
+    fn()                          # (one-time set-up behind a first call is not sustained work)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     while time.perf_counter() - t0 < 0.05:
         for _ in range(16):
