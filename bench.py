@@ -430,32 +430,37 @@ def bench_padded_linear(pit, wl, steps, warmup, pool=4):
     wsb = torch.empty(pit.pit_build_index_workspace(M, 1, 1, 1, 0), dtype=torch.uint8, device="cuda")
     Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
 
-    def step(i, zero=True):
-        pit.pit_build_index(masks[i % pool], 1, 1, 0, out=ix, ws=wsb)
-        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Y, zero_uncovered=zero)
-
-    sec = _time_steps(step, steps, warmup)
-    # the same step when the caller does not need the padding rows of the output cleared (SWrite touches
-    # the listed rows only; what follows in a padding-free model reads only those)
-    sec_nz = _time_steps(lambda i: step(i, False), steps, warmup)
-    # the same step with the output in the input type, as the dense comparator writes it (half the bytes stored
-    # and cleared; one rounding of the fp32 accumulator)
     Yb = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
 
-    def step_bf16(i):
-        pit.pit_build_index(masks[i % pool], 1, 1, 0, out=ix, ws=wsb)
-        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Yb, zero_uncovered=True)
+    def step_of(out, zero):
+        def step(i):
+            pit.pit_build_index(masks[i % pool], 1, 1, 0, out=ix, ws=wsb)
+            pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=out, zero_uncovered=zero)
+        return step
 
-    sec_bf = _time_steps(step_bf16, steps, warmup)
+    # The step that is reported: a bf16 linear layer with the padding rows of its output left zero, i.e. what the
+    # dense comparator delivers (bf16 output, every row defined), on the valid rows only.
+    sec = _time_steps(step_of(Yb, True), steps, warmup)
+    # the same with the fp32 accumulators stored as they are (twice the bytes stored and cleared)
+    sec_f32 = _time_steps(step_of(Y, True), steps, warmup)
+    # and when the caller does not need the padding rows cleared (SWrite touches the listed rows only; what
+    # follows in a padding-free model reads only those)
+    sec_nz = _time_steps(step_of(Yb, False), steps, warmup)
+    sec_f32_nz = _time_steps(step_of(Y, False), steps, warmup)
     dense_ms = _time_call(lambda: torch.matmul(X, W), 30)
-    # the product kernel alone on the last index (no index build, no clearing of the padding rows)
+    # the product kernel alone on the last index (no index build; the padding rows are cleared inside its launch)
     rows = int(ws[(warmup + steps - 1) % pool].lengths.sum())
-    k_s = _group_time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Y, zero_uncovered=False))
+    k_s = _group_time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Yb, zero_uncovered=True))
+    k_f32 = _group_time(lambda: pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=Y, zero_uncovered=True))
     return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": dense_ms, "dense_flops": 2.0 * M * K * N,
-            "extra": {"padding_rows_left_untouched_ms_per_step": round(sec_nz * 1e3, 4),
-                      "bf16_output_ms_per_step": round(sec_bf * 1e3, 4), "gemm_kernel_ms": round(k_s * 1e3, 4),
-                      "dense_comparator": "hipBLASLt bf16 GEMM over all 16384 rows, bf16 output (this path: fp32 output, padding rows cleared)",
-                      "roofline": _roofline("mfma", 2.0 * rows * K * N / k_s / 1e12, "k_gather_m_lds (bf16, fp32 C)")}}
+            "extra": {"output": "bf16, padding rows zero (as the dense comparator's)",
+                      "padding_rows_left_untouched_ms_per_step": round(sec_nz * 1e3, 4),
+                      "fp32_output_ms_per_step": round(sec_f32 * 1e3, 4),
+                      "fp32_output_padding_rows_left_untouched_ms_per_step": round(sec_f32_nz * 1e3, 4),
+                      "gemm_kernel_ms": round(k_s * 1e3, 4), "gemm_kernel_fp32_output_ms": round(k_f32 * 1e3, 4),
+                      "gemm_kernel_valid_rows": rows,
+                      "dense_comparator": "hipBLASLt bf16 GEMM over all 16384 rows, bf16 output",
+                      "roofline": _roofline("mfma", 2.0 * rows * K * N / k_s / 1e12, "k_gather_m_lds (bf16, bf16 C, clears the padding rows)")}}
 
 
 def bench_microtile(pit, wl, steps, warmup, pool=8):

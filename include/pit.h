@@ -259,7 +259,7 @@ typedef enum pit_gemm_mode {
  * GATHER_K and DENSE_K: mt in {32, 64, 128}, M % mt == 0.  Pointers 16-byte aligned, leading dimensions % 8 == 0.
  * Index entries outside the valid coordinate range are a caller error (not checked by this call:
  * see pit_check_index).  Grid limits (else PIT_ESHAPE): the worst-case number of row tiles of
- * GATHER_M, M / 128 + nseg, must not exceed 65528.
+ * GATHER_M, M / 128 + nseg, must not exceed 65520.
  */
 int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void* d_B, int64_t ldb,
                    void* d_C, int64_t ldc, int M, int N, int K, int in_dt, int c_dt,

@@ -648,36 +648,6 @@ k_slab_strip(const GemmArgs g) {
   }
 }
 
-// Zero rows of C that no index entry names (single-segment GATHER_M): the list is ascending, so a
-// row is uncovered iff a search for it misses.  One wave per row; the wave searches together, 64 probes per
-// round (three or four dependent loads for a list of thousands instead of a dozen), then stores 16 bytes per lane.
-template <int ESIZE>
-__global__ void __launch_bounds__(256)
-k_zero_uncovered(void* C, int64_t ldc, int M, int N, const int32_t* seg_ptr, const int32_t* idx) {
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= M) return;
-  const int lane = threadIdx.x & 63;
-  const int n = seg_ptr[1] - seg_ptr[0];
-  const int32_t* list = idx + seg_ptr[0];
-  // smallest j in [lo, hi) with list[j] >= row (hi if none)
-  int lo = 0, hi = n;
-  while (lo < hi) {
-    const int step = (hi - lo + 63) >> 6;
-    const int p = lo + lane * step;
-    const int v = p < hi ? list[p] : INT_MAX;
-    const int k = __builtin_popcountll(__ballot(v < row));     // the probes ascend: the first k are below the row
-    if (k == 0) { hi = lo; break; }
-    const int below = lo + (k - 1) * step;                       // last probe below the row
-    hi = min(hi, below + step);
-    lo = below + 1;
-  }
-  if (lo < n && list[lo] == row) return;
-  char* p = reinterpret_cast<char*>(C) + (int64_t)row * ldc * ESIZE;
-  const int64_t nbytes = (int64_t)N * ESIZE;
-  for (int64_t b = (int64_t)lane * 16; b < nbytes; b += 64 * 16)
-    *reinterpret_cast<uint4*>(p + b) = make_uint4(0, 0, 0, 0);
-}
-
 __global__ void __launch_bounds__(256) k_zero_rows(void* C, int64_t ld_bytes, int M, int64_t row_bytes) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= M) return;
@@ -792,11 +762,8 @@ extern "C" int pit_sread_gemm(int mode, const void* d_A, int64_t lda, const void
   if (lda < K) return PIT_EINVAL;
   g.slab = mt; g.a_gather = 1; g.c_scatter = 1; g.slab_per_seg = 1;
   if (ix->nseg == 1) {
-    if (zero_uncovered) {
-      if (c_esize == 4) hipLaunchKernelGGL(k_zero_uncovered<4>, dim3((unsigned)ceil_div(M, 4)), dim3(256), 0, st, d_C, ldc, M, N, ix->seg_ptr, ix->idx);
-      else              hipLaunchKernelGGL(k_zero_uncovered<2>, dim3((unsigned)ceil_div(M, 4)), dim3(256), 0, st, d_C, ldc, M, N, ix->seg_ptr, ix->idx);
-      PIT_LAUNCH_CHECK();
-    }
+    // (rows the list does not name are cleared inside the product's launch, by its workgroups without a tile)
+    g.zero_rest = zero_uncovered ? 1 : 0;
     return launch_gather_m(in_dt == PIT_BF16, EPI_STORE, c_dt != PIT_F32, g, M, st);
   }
   if (c_dt != PIT_F32) return PIT_EINVAL;

@@ -31,6 +31,7 @@
 // the row the index names (or to compact rows), optionally GELU + rounding to the input type.
 #include "pit_gemm.hpp"
 #include "pit_gemm_dev.hpp"
+#include <climits>
 #include <type_traits>
 
 namespace pit {
@@ -55,6 +56,43 @@ __device__ __forceinline__ uint2 lds_tr(uint32_t addr) {
 // the younger stages' loads stay in flight across it)
 #define PIT_LDS_BARRIER() do { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); __builtin_amdgcn_s_barrier(); \
                                asm volatile("" ::: "memory"); } while (0)
+
+// Zero the rows of C that an ascending list does not name, for the rows [r_begin, r_end): the share of one
+// workgroup without a tile (all of these shares together cover [0, M)).  One 64-ary search finds the list
+// position of the first row (three or four dependent loads for a list of thousands); from there the list is
+// read 64 entries at a time: the entries below the end of a chunk of 64 rows mark its covered rows in a 64-bit
+// mask, and as many entries as the mask has bits are consumed.  Wave w clears rows w, w + 4, ... of the chunk,
+// 16 bytes per lane.
+template <int ESIZE>
+__device__ __forceinline__ void zero_unlisted_rows(const GemmArgs& g, int r_begin, int r_end, int wv, int lane) {
+  const int n = g.seg_ptr[1] - g.seg_ptr[0];
+  const int32_t* list = g.idx + g.seg_ptr[0];
+  int lo = 0, hi = n;                      // smallest j with list[j] >= r_begin (n if none)
+  while (lo < hi) {
+    const int step = (hi - lo + 63) >> 6;
+    const int p = lo + lane * step;
+    const int v = p < hi ? list[p] : INT_MAX;
+    const int k = __builtin_popcountll(__ballot(v < r_begin));   // the probes ascend: the first k are below
+    if (k == 0) { hi = lo; break; }
+    const int below = lo + (k - 1) * step;
+    hi = min(hi, below + step);
+    lo = below + 1;
+  }
+  const int64_t nbytes = (int64_t)g.N * ESIZE;
+  for (int r0 = r_begin; r0 < r_end; r0 += 64) {
+    const int v = lo + lane < n ? list[lo + lane] : INT_MAX;     // strictly ascending: entry j is >= r0 + j
+    uint64_t m = (v < r0 + 64) ? (1ull << (v - r0)) : 0ull;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) m |= __shfl_xor(m, d);
+    lo += __builtin_popcountll(m);
+    for (int r = r0 + wv; r < min(r0 + 64, r_end); r += 4) {
+      if ((m >> (r - r0)) & 1) continue;
+      char* p = reinterpret_cast<char*>(g.C) + (int64_t)r * g.ldc * ESIZE;
+      for (int64_t b = (int64_t)lane * 16; b < nbytes; b += 64 * 16)
+        *reinterpret_cast<uint4*>(p + b) = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
 
 // GM x GN = arrangement of the four waves over the tile (2 x 2 or 1 x 4); a wave owns WM x WN blocks of 32 x 32.
 template <int WM, int WN, int NST, int GN> struct MTile {
@@ -85,15 +123,15 @@ k_gather_m_lds(const GemmArgs g) {
 
   // ---------------------------------------------------------------- which tile is this workgroup?
   // Consecutive workgroup ids go to different XCDs (8, each with its own L2).  The row tiles that exist (their
-  // number is known only here, from the segment lengths) are dealt out in 8 contiguous shares, one per XCD, and
-  // an XCD runs all column tiles of a row tile back to back: the column tiles read the same gathered A rows,
-  // and neighbouring row tiles of one segment (one expert) read the same B, through the same L2.  The grid is
-  // sized for the worst case; workgroups beyond an XCD's share leave at once.
+  // number is known only here, from the segment lengths) are dealt out in contiguous shares and each XCD works
+  // through its share in order, all its column tiles of a row tile back to back: they read the same gathered A
+  // rows, and neighbouring row tiles of one segment (one expert) read the same B, through the same L2.  The grid
+  // is sized for the worst case; workgroups beyond an XCD's share have no tile.
   const int tn = gridDim.x;
   const int lin = blockIdx.x + tn * blockIdx.y;
   const int xcd = lin & 7, slot = lin >> 3;
-  const int tile_col = slot % tn, row_in_share = slot / tn;
-  const int n0 = tile_col * TNW;
+  const int row_in_share = slot / tn;
+  int n0 = (slot % tn) * TNW;
   // One pass over the segment lengths gives the number of row tiles and, in the same registers, the segment and
   // position of this workgroup's tile (up to 64 segments: one load per lane; more: a second pass).  Every load
   // here is a round trip to memory on the critical path of the tile, so nothing is fetched twice.
@@ -123,9 +161,32 @@ k_gather_m_lds(const GemmArgs g) {
     int beg, cnt, nt;
     const int inc = scan64(0, beg, cnt, nt);
     total_tiles = __shfl(inc, 63);
-    const int share = (total_tiles + 7) >> 3;
-    const int tile = xcd * share + row_in_share;
-    if (row_in_share >= share || tile >= total_tiles) return;
+    // The 8 XCDs form XR row groups x XC column groups (XC = g.xcd_cols, set by the launcher): an XCD works on
+    // tn / XC column tiles of a contiguous share of the row tiles.  XC = 1 (every segment has a B of its own): an
+    // XCD runs all column tiles of a row tile back to back.  XC > 1 (one B for all row tiles): an XCD's slice of
+    // B stays in its L2 for the whole launch and only A rows stream through.
+    const int xcn = g.xcd_cols, xrn = 8 / xcn;
+    const int xr = xcd % xrn, xc = xcd / xrn;
+    const int share = (total_tiles + xrn - 1) / xrn;
+    const int cpx = tn / xcn;                      // column tiles an XCD works on
+    const int mine = share * cpx;                  // tile slots of an XCD
+    // Slots of an XCD beyond its tiles have no work and come last in dispatch order, so they run beside the last,
+    // partly filled round of tiles.  With zero_rest they clear the unlisted rows of C meanwhile, each an equal
+    // share of the rows (their number grows with the number of unlisted rows: both are what the worst-case grid
+    // has left over).  (Placed behind the first round of tiles instead, so that their stores drain under the
+    // second round's loops: the padded-batch step 3 us slower with bf16 output, 2 us faster with fp32 output.)
+    if (slot >= mine) {
+      if (g.zero_rest) {
+        const int idle = (int)(gridDim.x * gridDim.y / 8) - mine;
+        const int d = (slot - mine) * 8 + xcd, per = (g.M + 8 * idle - 1) / (8 * idle);
+        const int rb = min(g.M, d * per), re = min(g.M, rb + per);
+        if (rb < re) zero_unlisted_rows<CT ? 2 : 4>(g, rb, re, wv, lane);
+      }
+      return;
+    }
+    const int tile = xr * share + slot / cpx;
+    n0 = (xc * cpx + slot % cpx) * TNW;
+    if (tile >= total_tiles) return;
     locate(tile, 0, inc, nt, beg, cnt, 0);
   } else {
     for (int s0 = 0; s0 < g.nseg; s0 += 64) {
@@ -389,12 +450,20 @@ k_gather_m_lds(const GemmArgs g) {
 }
 
 template <bool BF, int EPI, int CT, int WM, int WN, int NST, int GN = 2>
-int launch_cfg(const GemmArgs& g, int64_t total_rows, hipStream_t st) {
+int launch_cfg(GemmArgs g, int64_t total_rows, hipStream_t st) {
   using T = MTile<WM, WN, NST, GN>;
+  // One B for all row tiles: 2 row groups x 4 column groups of XCDs where the number of column tiles allows
+  // (padded batch, 16 column tiles: 96 us per step with 8 x 1, 88-89 us with 4 x 2, 2 x 4 and 1 x 8).
+  g.xcd_cols = 1;
+  if (g.nseg == 1) {
+    const int tn = g.N / T::TNW;
+    g.xcd_cols = tn % 4 == 0 ? 4 : tn % 2 == 0 ? 2 : 1;
+  }
   const int64_t max_tiles = total_rows / T::TMW + g.nseg;      // sum over segments of ceil(count / TMW)
-  if (max_tiles > 65528) return PIT_ESHAPE;
-  // (row tiles rounded up to a multiple of 8: every XCD then has room for its share of the tiles that exist)
-  dim3 grid((unsigned)(g.N / T::TNW), (unsigned)((max_tiles + 7) & ~(int64_t)7));
+  if (max_tiles > 65520) return PIT_ESHAPE;
+  // (row tiles rounded up to a multiple of 8: every XCD then has room for its share of the tiles that exist;
+  // with zero_rest one more row of workgroups per XCD, so that some are without a tile whatever the list holds)
+  dim3 grid((unsigned)(g.N / T::TNW), (unsigned)(((max_tiles + 7) & ~(int64_t)7) + (g.zero_rest ? 8 : 0)));
   hipLaunchKernelGGL((k_gather_m_lds<BF, EPI, CT, WM, WN, NST, GN>), grid, dim3(256), 0, st, g);
   PIT_LAUNCH_CHECK();
   return PIT_OK;
@@ -429,6 +498,7 @@ int launch_bf(int epi, int ct, const GemmArgs& g, int64_t total_rows, hipStream_
 int launch_gather_m(bool bf, int epi, int c_is_in_type, const GemmArgs& g, int64_t total_rows, hipStream_t st) {
   if (total_rows <= 0 || g.N <= 0 || g.nseg <= 0) return PIT_OK;
   if (g.slab % 32 || g.N % 128) return PIT_ESHAPE;
+  if (g.zero_rest && (g.nseg != 1 || !g.c_scatter)) return PIT_EINVAL;
   // the kernel addresses each operand with 32-bit byte offsets from a per-segment base and multiplies
   // row numbers by the row pitch in 24 bits
   if (g.lda * 2 >= (1ll << 24) || g.ldb * 2 >= (1ll << 24) || (int64_t)g.M >= (1ll << 24) || (int64_t)g.K >= (1ll << 24)) return PIT_ESHAPE;

@@ -237,6 +237,33 @@ def test_padded_linear_degenerate_masks(pit):
         assert np.array_equal(Y.cpu().numpy().astype(np.float64), orc.gemm_rows_masked(w.X, w.row_mask, w.W))
 
 
+@pytest.mark.parametrize("batch,max_len,min_len,out", [
+    (8, 512, 480, 128),      # nearly all rows listed: 16 workgroups without a tile clear 256 rows each (4 chunks of 64)
+    (8, 512, 1, 128),        # about half of the rows listed
+    (16, 256, 1, 256),
+    (64, 250, 240, 512),     # the wide tile; M = 16000 is not a multiple of the tile height
+    (1, 100, 3, 128),        # fewer rows than one tile, three of them listed
+])
+def test_padded_linear_every_unlisted_row_is_cleared(pit, batch, max_len, min_len, out):
+    """The rows the list does not name are cleared by the product's own launch (its workgroups without a
+    tile share the rows of C among them): every element of C is compared, from a sentinel-filled buffer, in
+    both output types."""
+    w = wl.padded_linear(batch=batch, max_len=max_len, hidden=64, out=out, min_len=min_len, seed=batch + out, integer=True)
+    w.X[w.row_mask == 0] = 0x7FC0
+    ref = orc.gemm_rows_masked(w.X, w.row_mask, w.W)
+    Y = _run_padded(pit, w, sentinel=55.0)
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref)
+    X, W, mask = to_dev(w.X), to_dev(w.W), to_dev(w.row_mask.reshape(-1, 1))
+    M, K = w.X.shape
+    ix = pit.pit_build_index(mask, 1, 1, 0)
+    outb = torch.full((M, out), 3.0, dtype=torch.bfloat16, device=dev())
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, out, K, out=outb, zero_uncovered=True)
+    torch.cuda.synchronize()
+    got = orc.bf16_bits_to_f64(bf16_bits(outb))
+    assert not got[w.row_mask == 0].any()
+    assert np.all(np.abs(got[w.row_mask == 1] - orc.round_to_bf16(ref[w.row_mask == 1])) <= np.abs(ref[w.row_mask == 1]) * 2.0 ** -7)
+
+
 def test_padded_linear_bf16_output(pit):
     """Output in the input type (what the next layer of a bf16 model reads): listed rows within one bf16
     ulp of the rounded oracle, padding rows exactly zero, also from a sentinel-filled buffer."""
