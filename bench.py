@@ -373,15 +373,16 @@ def bench_sweep_4096(pit, wl, steps, warmup):
     return {"dense_ms": round(dense_s * 1e3, 4), "points": pts}
 
 
-def bench_relu_producer(pit, wl, steps, warmup, pool=4):
+def bench_relu_producer(pit, wl, steps, warmup, pool=4, live_prob=0.25):
     """The headline product fed from the pre-activation H[tokens][channels] (what the up-projection leaves
     in HBM): ReLU, the change to the channel-major layout and the detection in one pass over H
     (pit_relu_channel_major_index), against the same work done as an elementwise ReLU + transposed copy
-    followed by pit_build_index.  Zeros correlated across tokens as in relu_ffn_correlated_zeros."""
+    followed by pit_build_index.  Zeros correlated across tokens as in relu_ffn_correlated_zeros, or
+    (live_prob None) independent as in the headline workload."""
     import numpy as np
     import torch
     M, K, N, MT = 2048, 8192, 2048, 128
-    Hs_np = [wl.relu_ffn_preactivation(M=M, K=K, call=c, channel_live_prob=0.25) for c in range(pool)]
+    Hs_np = [wl.relu_ffn_preactivation(M=M, K=K, call=c, channel_live_prob=live_prob) for c in range(pool)]
     Hs = [_to_dev(h) for h in Hs_np]
     W = _to_dev(wl.relu_ffn(M=8, K=K, N=N, call=0).W)
     relu_bits = [np.where((h & 0x8000) != 0, 0, h).astype(np.uint16) for h in Hs_np]      # finite data: sign test
@@ -410,8 +411,18 @@ def bench_relu_producer(pit, wl, steps, warmup, pool=4):
     sec_unfused = _time_steps(unfused, steps, warmup)
     sec_dense = _time_steps(dense, steps, warmup)
     sec_producer = _time_steps(lambda i: pit.pit_relu_channel_major_index(Hs[i % pool], out_xt=Xt, out=ix, ws=wsb), steps, warmup)
+    # what the index costs on this path: the same step with the index left as the previous call wrote it (the
+    # producer still does ReLU, layout change and bitmap; the emit pass is what falls away)
+    def no_index(i):
+        pit.pit_relu_channel_major_index(Hs[i % pool], out_xt=Xt, ws=wsb, index=False)
+        pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_K, Xt, W, ix, MT, M, N, K, out=C)
+
+    pit.pit_relu_channel_major_index(Hs[0], out_xt=Xt, out=ix, ws=wsb)
+    sec_no_index = _time_steps(no_index, steps, warmup)
     return {"sec_per_step": sec, "eff_flops": eff, "dense_ms": sec_dense * 1e3,
             "extra": {"unfused_ms_per_step": round(sec_unfused * 1e3, 4), "producer_ms": round(sec_producer * 1e3, 4),
+                      "ms_per_step_without_emitting_the_index": round(sec_no_index * 1e3, 4),
+                      "index_share_of_step": round(max(0.0, sec - sec_no_index) / sec, 4),
                       "producer_GB_per_s": round(2.0 * M * K * 2 / sec_producer / 1e9, 1),
                       "dense_comparator": "torch.relu + hipBLASLt matmul on the token-major tensor"}}
 
@@ -608,6 +619,7 @@ def main():
             ("relu_ffn_dead_runs_of_32_tokens", lambda p_, w_, k_, u_: bench_relu_ffn_correlated(p_, w_, k_, u_, live_block=32)),
             ("relu_ffn_dead_runs_of_128_at_offset_64", lambda p_, w_, k_, u_: bench_relu_ffn_correlated(p_, w_, k_, u_, live_offset=64)),
             ("relu_ffn_from_preactivation", bench_relu_producer),
+            ("relu_ffn_headline_from_preactivation", lambda p_, w_, k_, u_: bench_relu_producer(p_, w_, k_, u_, live_prob=None)),
             ("microtile_1x32_1024", bench_microtile), ("moe_switch_4096x64", bench_moe),
             ("padded_batch_32x512", bench_padded_linear), ("sparse_attn_4096x12x64", bench_attn)]
     if args.side is not None:

@@ -153,6 +153,8 @@ size_t pit_relu_channel_major_index_workspace(int tokens, int channels);
  *            NaN is passed through unchanged (and counts as non-zero), +Inf stays.
  *   tokens   multiple of 128;  channels  multiple of 8;  ldh, ldxt multiples of 8; d_H, d_Xt 16-byte aligned.
  *   out      out->nseg == tokens / 128, out->cap >= (tokens / 128) * channels, out->bits NULL.
+ *            NULL: no index is written (ReLU and layout change only; the workspace is still needed) --
+ *            what the detection adds to the pass can be timed as the difference.
  *   d_ws     workspace of at least pit_relu_channel_major_index_workspace(...) bytes, 8-byte aligned.
  * d_H and d_Xt must not overlap.  Errors as for pit_build_index.  tokens*channels == 0 is not an error.
  */

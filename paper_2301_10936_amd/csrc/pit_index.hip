@@ -1075,16 +1075,17 @@ extern "C" size_t pit_relu_channel_major_index_workspace(int tokens, int channel
 extern "C" int pit_relu_channel_major_index(const void* d_H, int64_t ldh, int tokens, int channels, int dt,
                                             void* d_Xt, int64_t ldxt, const pit_index* out,
                                             void* d_ws, size_t ws_bytes, pit_stream stream) {
-  if (!out || !out->seg_ptr || out->bits || (dt != PIT_BF16 && dt != PIT_F16)) return PIT_EINVAL;
+  // out == nullptr: ReLU and layout change only (the bitmap still goes to the workspace, nothing is emitted)
+  if ((out && (!out->seg_ptr || out->bits)) || (dt != PIT_BF16 && dt != PIT_F16)) return PIT_EINVAL;
   if (tokens < 0 || channels < 0 || tokens % 128 || channels % 8) return PIT_ESHAPE;
   // the index of Xt[channels][tokens] at 1 x 128 micro-tiles with the channel as PIT coordinate
   const Layout L = make_layout(channels, tokens, 1, 128, 0, 0);
-  if (out->nseg != L.nseg) return PIT_ECAPACITY;
-  if ((int64_t)out->cap < (int64_t)L.nseg * L.npit) return PIT_ECAPACITY;
+  if (out && out->nseg != L.nseg) return PIT_ECAPACITY;
+  if (out && (int64_t)out->cap < (int64_t)L.nseg * L.npit) return PIT_ECAPACITY;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  if (L.nseg == 0 || L.npit == 0) return launch_emit(L, nullptr, nullptr, nullptr, out, 0, nullptr, st);
+  if (L.nseg == 0 || L.npit == 0) return out ? launch_emit(L, nullptr, nullptr, nullptr, out, 0, nullptr, st) : PIT_OK;
   if (ldh < channels || ldxt < tokens || ldh % 8 || ldxt % 8) return PIT_EINVAL;
-  if (!d_H || !d_Xt || !out->idx || !d_ws || !aligned(d_ws, 8) || !aligned(d_H, 16) || !aligned(d_Xt, 16)) return PIT_EINVAL;
+  if (!d_H || !d_Xt || (out && !out->idx) || !d_ws || !aligned(d_ws, 8) || !aligned(d_H, 16) || !aligned(d_Xt, 16)) return PIT_EINVAL;
   if (ws_bytes < pit_relu_channel_major_index_workspace(tokens, channels)) return PIT_ECAPACITY;
   if (tokens / 128 > 65535) return PIT_ESHAPE;
 
@@ -1099,7 +1100,7 @@ extern "C" int pit_relu_channel_major_index(const void* d_H, int64_t ldh, int to
     hipLaunchKernelGGL(k_relu_transpose_bitmap<false>, grid, dim3(256), 0, st, d_H, ldh * 2, tokens, channels, d_Xt,
                        ldxt * 2, L.W, reinterpret_cast<uint32_t*>(words));
   PIT_LAUNCH_CHECK();
-  return launch_emit(L, words, cnt, nullptr, out, 0, nullptr, st);
+  return out ? launch_emit(L, words, cnt, nullptr, out, 0, nullptr, st) : PIT_OK;
 }
 
 // The count does not depend on the PIT-axis; byte masks with column-shaped micro-tiles take the

@@ -218,25 +218,28 @@ def pit_relu_channel_major_index_workspace(tokens, channels) -> int:
 
 
 def pit_relu_channel_major_index(H: torch.Tensor, out_xt: torch.Tensor | None = None, out: PitIndex | None = None,
-                                 ws: torch.Tensor | None = None):
+                                 ws: torch.Tensor | None = None, index: bool = True):
     """Xt = ReLU(H)^T ([channels, tokens]) and its index at 1 x 128 micro-tiles in one pass over H
-    ([tokens, channels], last dim contiguous).  Returns (Xt, index).  See include/pit.h."""
+    ([tokens, channels], last dim contiguous).  Returns (Xt, index); with index=False no index is
+    written and (Xt, None) is returned.  See include/pit.h."""
     assert H.dim() == 2 and H.stride(1) == 1
     tokens, channels = H.shape
     if out_xt is None:
         out_xt = torch.empty((channels, tokens), dtype=H.dtype, device=H.device)
-    if out is None:
+    if not index:
+        out = None
+    elif out is None:
         if tokens % 128:
             raise PitError(PIT_ESHAPE, "pit_relu_channel_major_index")
         out = PitIndex.empty(tokens // 128, (tokens // 128) * channels, False, H.device)
     if ws is None:
         ws = torch.empty(max(pit_relu_channel_major_index_workspace(tokens, channels), 8), dtype=torch.uint8,
                          device=H.device)
-    ci = out.c()
+    ci = out.c() if out is not None else None
     _check(_lib.pit_relu_channel_major_index(H.data_ptr(), H.stride(0) if tokens > 1 else max(channels, H.stride(0)),
                                              tokens, channels, _dt(H), out_xt.data_ptr(),
                                              out_xt.stride(0) if channels > 1 else max(tokens, out_xt.stride(0)),
-                                             ctypes.byref(ci), ws.data_ptr(), ws.numel(), _stream()),
+                                             ctypes.byref(ci) if ci is not None else None, ws.data_ptr(), ws.numel(), _stream()),
            "pit_relu_channel_major_index")
     return out_xt, out
 

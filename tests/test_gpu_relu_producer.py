@@ -95,6 +95,17 @@ def test_feeds_the_gather_k_product(pit):
     assert np.array_equal(C.cpu().numpy().astype(np.float64), np.maximum(orc.to_f64(H), 0) @ orc.to_f64(W))
 
 
+def test_without_an_index_the_layout_change_is_the_same(pit):
+    """index=False (out == NULL at the C ABI): the same Xt, bit for bit, and nothing else is written."""
+    g = np.random.default_rng(77)
+    H_np = wl.to_bf16_bits(_pre_activation(g, 384, 200))
+    Xt, none = pit.pit_relu_channel_major_index(to_dev(H_np), index=False)
+    torch.cuda.synchronize()
+    assert none is None
+    want_xt, _, _ = orc.relu_channel_major(H_np, 128)
+    assert np.array_equal(Xt.view(torch.int16).cpu().numpy().view(np.uint16), want_xt.view(np.uint16))
+
+
 def test_empty_and_error_returns(pit):
     lib, _ = pit.raw()
     e = torch.empty((0, 64), dtype=torch.bfloat16, device=dev())
