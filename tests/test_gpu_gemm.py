@@ -290,6 +290,29 @@ def test_c4_full_size(pit):
     assert torch.count_nonzero(Y[to_dev(w.row_mask) == 0]) == 0
 
 
+def test_c4_full_size_bf16_output(pit):
+    """The configuration bench.py times for the padded batch: bf16 output, padding rows cleared inside the
+    product's launch.  Every element is compared (listed rows against the oracle rounded to bf16, within one
+    bf16 step plus the accumulation tolerance; padding rows exactly zero), from a sentinel-filled buffer."""
+    w = wl.padded_linear()
+    X, W, mask = to_dev(w.X), to_dev(w.W), to_dev(w.row_mask.reshape(-1, 1))
+    M, K = w.X.shape
+    N = w.W.shape[1]
+    ix = pit.pit_build_index(mask, 1, 1, 0)
+    out = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=dev())
+    pit.pit_sread_gemm(pit.PIT_GEMM_GATHER_M, X, W, ix, K, M, N, K, out=out, zero_uncovered=True)
+    torch.cuda.synchronize()
+    # the output's own rounding (up to 2^-9 relative, 1.1e-3 rms) is not the product's error: the oracle is
+    # rounded the same way, and the kernel's fp32 sum may land one bf16 step beside it
+    want = orc.round_to_bf16(orc.gemm_rows_masked(w.X, w.row_mask, w.W))
+    assert_close(out, want, "C4 full size, bf16 output")
+    assert torch.count_nonzero(out[to_dev(w.row_mask) == 0]) == 0
+    got = orc.bf16_bits_to_f64(bf16_bits(out))
+    live = w.row_mask == 1
+    scale = np.sqrt(np.mean(want[live] ** 2))
+    assert np.all(np.abs(got[live] - want[live]) <= np.abs(want[live]) * 2.0 ** -7 + scale * 1e-3)
+
+
 # ------------------------------------------------------------------ GATHER_M, k-slabs (1 x 32 micro-tiles)
 def _run_microtile(pit, w, mt=32):
     A, B = to_dev(w.A), to_dev(w.B)
