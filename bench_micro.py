@@ -89,8 +89,9 @@ def sweep_point(pit, At, B, n, reps, cands, t_dense_lib):
 
 
 def probe():
-    """Register-resident issue rate of the two MFMA shapes the kernels use (1 and 4 waves per SIMD), an empty
-    kernel's launch, and three dependent launches back to back (the floor of a three-kernel step)."""
+    """Register-resident issue rate of the two MFMA shapes the kernels use (1 and 4 waves per SIMD), the rate at
+    which a read-only kernel streams a mixture-of-experts matmul's weights, an empty kernel's launch, and three
+    dependent launches back to back (the floor of a three-kernel step)."""
     import ctypes
     here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2301_10936_amd")
     lib = ctypes.CDLL(os.path.join(here, "libpit_probe.so"))
@@ -113,6 +114,34 @@ def probe():
             per = t / (iters * 8.0) * 1e9
             res["mfma"].append({"instruction": name, "waves_per_simd": waves_per_simd, "TFLOP_per_s": round(flops[0] / t / 1e12, 1),
                                 "ns_per_mfma_per_wave": round(per, 2)})
+    # Streaming of the 302 MB of one MoE matmul's expert weights (read once per call; two such buffers alternate,
+    # as the two matmuls of the call do, so nothing is left in the 256 MB Infinity Cache from the launch before):
+    # contiguous ranges from a growing number of workgroups, and the 512-byte pieces of rows that a 256-column tile
+    # of matmul 2 (3072 x 256 of an expert's 3072 x 768) and of matmul 1 (768 x 256 of 768 x 3072) reads
+    lib.pit_probe_stream.restype = ctypes.c_double
+    lib.pit_probe_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_long, ctypes.c_long,
+                                     ctypes.c_int, ctypes.c_int, ctypes.c_long, ctypes.c_void_p, ctypes.c_void_p]
+    half = 64 * 3072 * 768 * 2
+    buf = torch.zeros(2 * half, dtype=torch.uint8, device="cuda")
+    cases = []
+    for wgs in (256, 512, 1024, 4096):
+        per = (half // wgs) // 16384 * 16384
+        cases.append((f"contiguous, {per >> 10} KB per workgroup", wgs, wgs, 0, per, per // 512, 512))
+    cases.append(("matmul 2 tiles: 3072 pieces of 512 B at pitch 1536 B", 192, 3, 3072 * 1536, 512, 3072, 1536))
+    cases.append(("matmul 1 tiles: 768 pieces of 512 B at pitch 6144 B", 768, 12, 768 * 6144, 512, 768, 6144))
+    res["stream_302MB"] = []
+    for name, wgs, per_group, gstride, wstride, rows, pitch in cases:
+        flip, nbytes = [0], [0.0]
+
+        def run():
+            flip[0] ^= 1
+            nbytes[0] = lib.pit_probe_stream(buf.data_ptr() + flip[0] * half, half, wgs, per_group, gstride, wstride, rows, 512, pitch,
+                                             out.data_ptr(), st)
+
+        t = _time(run, 20)
+        if nbytes[0] <= 0:
+            raise RuntimeError("pit_probe_stream rejected " + name)
+        res["stream_302MB"].append({"pattern": name, "workgroups": wgs, "us": round(t * 1e6, 1), "TB_per_s": round(nbytes[0] / t / 1e12, 2)})
     res["launch"]["empty_kernel_us"] = round(_time(lambda: lib.pit_probe_empty(st), 200) * 1e6, 2)
     res["launch"]["three_dependent_empty_kernels_us"] = round(_time(lambda: [lib.pit_probe_empty(st) for _ in range(3)], 100) * 1e6, 2)
     print(json.dumps(res, indent=1))
