@@ -122,12 +122,16 @@ def _group_time(fn, groups=4, per_group=8):
     return sum(ev[2 * gi].elapsed_time(ev[2 * gi + 1]) for gi in range(groups)) / (groups * per_group) * 1e-3
 
 
-def _roofline(bound, achieved, kernel, note=None):
+def _roofline(bound, achieved, kernel, note=None, profile=None):
     """A roofline block like the headline's for one of the other workloads: the dominant kernel's algorithmic
-    FLOPs (or bytes) per launch over its duration measured in this run."""
+    FLOPs (or bytes) per launch over its duration measured in this run; `traffic` = HBM bytes per launch from the
+    committed rocprofv3 summary `profile` (not measured in this run), None without one."""
     peak, unit = (MFMA_PEAK_TFLOPS, "TFLOP/s") if bound == "mfma" else (HBM_PEAK_GBS, "GB/s")
+    traffic = _read_traffic(profile) if profile else None
     r = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-         "frac": round(achieved / peak, 4), "traffic": None, "traffic_source": None}
+         "frac": round(achieved / peak, 4), "traffic": traffic,
+         "traffic_source": (f"profiles/{profile} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of a committed run, not measured in this run)"
+                            if traffic is not None else None)}
     if note:
         r["note"] = note
     return r
@@ -471,7 +475,8 @@ def bench_padded_linear(pit, wl, steps, warmup, pool=4):
                       "gemm_kernel_ms": round(k_s * 1e3, 4), "gemm_kernel_fp32_output_ms": round(k_f32 * 1e3, 4),
                       "gemm_kernel_valid_rows": rows,
                       "dense_comparator": "hipBLASLt bf16 GEMM over all 16384 rows, bf16 output",
-                      "roofline": _roofline("mfma", 2.0 * rows * K * N / k_s / 1e12, "k_gather_m_lds (bf16, bf16 C, clears the padding rows)")}}
+                      "roofline": _roofline("mfma", 2.0 * rows * K * N / k_s / 1e12, "k_gather_m_lds (bf16, bf16 C, clears the padding rows)",
+                                            profile="k_gather_m_lds_padded_batch.txt")}}
 
 
 def bench_microtile(pit, wl, steps, warmup, pool=8):
@@ -534,7 +539,8 @@ def bench_moe(pit, wl, steps, warmup, pool=4):
             "extra": {"dense_comparator": "capacity-padded batched matmul (every expert padded to the busiest one)",
                       "dense_ffn_same_flops_one_expert_ms": round(same_s * 1e3, 4),
                       "roofline": _roofline("hbm", weight_bytes / sec / 1e9, "pit_moe_dispatch_gemm (route index + 2 x k_gather_m_lds)",
-                                            "604 MB of expert weights per pass over the whole call's time")}}
+                                            "604 MB of expert weights per pass over the whole call's time",
+                                            profile="k_gather_m_lds_moe_switch.txt")}}
 
 
 def bench_attn(pit, wl, steps, warmup, pool=4):
@@ -559,7 +565,8 @@ def bench_attn(pit, wl, steps, warmup, pool=4):
     extra = {"dense_comparator": "unfused torch baddbmm + fp32 softmax + matmul with an additive mask",
              "gathered_KV_GB_per_s": round(2.0 * H * kept * D * 2 / sec / 1e9, 1),
              "roofline": _roofline("mfma", eff / sec / 1e12, "pit_sparse_attn (index of the mask + k_sparse_attn)",
-                                   "bound by the gather of K/V rows out of L2 (gathered_KV_GB_per_s) and vector-ALU softmax work, not by the matrix pipe")}
+                                   "bound by the gather of K/V rows out of L2 (gathered_KV_GB_per_s) and vector-ALU softmax work, not by the matrix pipe",
+                                   profile="k_sparse_attn_4096x12x64.txt")}
     try:   # a fused dense comparator, if the library offers one for this mask
         bm = masks[0].to(torch.bool)
         f = torch.nn.functional.scaled_dot_product_attention
