@@ -32,6 +32,8 @@ struct GemmArgs {
   int a_gather;      // GATHER_M: 1 = A rows come from idx, 0 = A rows are seg_ptr[s] + r (compact)
   int c_scatter;     // GATHER_M: 1 = C rows go to idx, 0 = C rows are seg_ptr[s] + r (compact)
   int slab_per_seg;  // GATHER_M: 1 = segment s covers k in [s*slab, (s+1)*slab), 0 = every segment covers [0, K)
+  int k_stagger;     // GATHER_M, set by the launcher: 1 = tiles of different segments / column tiles start their walk
+                     // over k at different steps (per-segment B)
   int xcd_cols;      // GATHER_M, set by the launcher: the 8 XCDs form 8 / xcd_cols row groups x xcd_cols column groups
   int zero_rest;     // GATHER_M, one segment: 1 = the rows of C that the list does not name are set to zero by the
                      // workgroups of the grid that have no tile
